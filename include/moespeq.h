@@ -1,0 +1,255 @@
+/*
+ * moespeq.h -- C ABI of the MI355X (gfx950) MoE-layer library for MoE-SpeQ-style speculative
+ * quantized decoding (arXiv 2511.14102).
+ *
+ * The library runs the Mixture-of-Experts layer forward of the paper's execution engine
+ * (section 3.4): once per draft step on group-wise int4 expert weights, emitting the
+ * expert-id sets that fill the Expert Lookahead Buffer (section 3.3.1), and once per verify
+ * step in bf16 over the K+1 speculative tokens against experts held in a VRAM expert cache
+ * that is addressed through a slot table (sections 3.3.2, 3.4.4).
+ *
+ * General rules
+ *  - Plain C linkage, plain pointers and sizes.  Unless a parameter says "host", every data
+ *    pointer is a DEVICE pointer owned by the caller; the library keeps no pointer after a
+ *    call returns and allocates nothing per call (section 4.1.2: no run-time allocation in
+ *    the hot path).  `stream` parameters are hipStream_t handles passed as void* (NULL = the
+ *    default stream); events are hipEvent_t handles passed as void*.
+ *  - Every call validates its arguments on the host, enqueues its kernels on `stream` and
+ *    returns; outputs are valid once the stream has reached that point.  No call
+ *    synchronises, except moe_verify_layer_bf16 with MOE_VERIFY_STRICT.
+ *  - Return value: MOE_OK or a negative status.  On MOE_ERR_INVALID_ARG / MOE_ERR_WORKSPACE
+ *    nothing has been enqueued.  After MOE_ERR_HIP, moe_last_hip_error() names the HIP error.
+ *  - Inputs must be finite; NaN / Inf activations or weights give unspecified outputs.
+ *  - One moe_ctx may be used from one host thread at a time.  Calls that share a workspace
+ *    must be ordered on one stream (or by events).
+ *
+ * Shapes: T tokens, H hidden, E routed experts, I intermediate (SwiGLU), k top-k, g int4 group
+ * size, S shared experts.  Assignment index a = t * k + j (token-major, j = rank).
+ * Limits: 1 <= T <= MOE_MAX_TOKENS (draft: MOE_MAX_DRAFT_TOKENS), E <= MOE_MAX_EXPERTS,
+ * k <= min(E, MOE_MAX_TOPK), T * k <= MOE_MAX_ASSIGN, S <= MOE_MAX_SHARED, H and I multiples
+ * of 64, g in {32, 64, 128} dividing both H and I.
+ *
+ * Kernel-native weight layouts (part of the ABI; pack.py builds them from row-major arrays)
+ *
+ *  bf16 matrix W[R][C] (R outputs, C inputs; R % 16 == 0, C % 32 == 0), "tile16x32":
+ *      a sequence of 1 KiB tiles, tile index (R/16-major) tile = (r / 16) * (C / 32) + c / 32;
+ *      inside a tile 64 lanes x 8 bf16:  lane = ((c % 32) / 8) * 16 + r % 16,  element c % 8.
+ *      (This is the A-operand register image of the 16x16x32 bf16 MFMA, so one 16-byte load
+ *      per lane fetches one tile.)
+ *  bf16 expert blob = [gate I x H | up I x H | down H x I], each tile16x32, contiguous,
+ *      moe_bf16_expert_bytes() bytes.  One blob fills one slot of the expert cache.
+ *
+ *  int4 matrix, codes q[R][C] in 0..15, fp16 scale s and zero z per (row, group of g
+ *  consecutive inputs), W = (q - z) * s  (R % 64 == 0, C % 32 == 0), "tile64x32":
+ *      codes: 1 KiB tiles, tile = (r / 64) * (C / 32) + c / 32; inside a tile lane = r % 64
+ *      owns 16 bytes = 4 little-endian 32-bit words; word d holds the 8 codes
+ *      c % 32 in [8d, 8d + 8); code number n of the word (n = c % 8) sits in bits
+ *      [4 * p, 4 * p + 4) with p = n / 2 for even n and p = 4 + n / 2 for odd n.
+ *      scale/zero: for tile row-block r / 64 and group c / g, 64 lanes x (fp16 s, fp16 z):
+ *      index ((r / 64) * (C / g) + c / g) * 64 + r % 64, 4 bytes each (s in the low half).
+ *  int4 expert = codes blob [gate | up | down] of moe_int4_expert_q_bytes() bytes and
+ *      scale/zero blob [gate | up | down] of moe_int4_expert_sz_bytes() bytes.
+ */
+#ifndef MOESPEQ_H
+#define MOESPEQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_MAX_TOKENS        16
+#define MOE_MAX_DRAFT_TOKENS  8
+#define MOE_MAX_EXPERTS       256
+#define MOE_MAX_TOPK          16
+#define MOE_MAX_ASSIGN        128
+#define MOE_MAX_SHARED        4
+
+#define MOE_OK                   0
+#define MOE_ERR_INVALID_ARG     (-1)
+#define MOE_ERR_WORKSPACE       (-2)
+#define MOE_ERR_HIP             (-3)
+#define MOE_ERR_MISSING_EXPERT  (-4)
+
+/* flags of moe_verify_layer_bf16 */
+#define MOE_VERIFY_ACCUMULATE   1   /* y += result instead of y = result                    */
+#define MOE_VERIFY_ONLY_LISTED  2   /* only experts listed in `missing` on entry; no shared */
+#define MOE_VERIFY_STRICT       4   /* synchronise; MOE_ERR_MISSING_EXPERT if any is absent */
+
+typedef struct moe_ctx moe_ctx;      /* opaque: device number and properties, no weights */
+
+typedef struct moe_layer_desc {
+    int32_t hidden;        /* H */
+    int32_t n_experts;     /* E routed experts */
+    int32_t inter;         /* I */
+    int32_t top_k;         /* k */
+    int32_t n_shared;      /* S always-on shared experts (bf16 in both passes) */
+    int32_t group_size;    /* g (draft only; ignored by route / verify) */
+    int32_t renormalize;   /* nonzero: routing weights divided by their sum over the k */
+} moe_layer_desc;
+
+/* Routed experts of the draft model: expert e's codes at q + e * expert_stride_q, its
+ * scale/zero blob at sz + e * expert_stride_sz (device pointers, 16-byte aligned strides). */
+typedef struct moe_int4_experts {
+    const void *q;
+    const void *sz;
+    size_t expert_stride_q;
+    size_t expert_stride_sz;
+} moe_int4_experts;
+
+/* ---- context and helpers (host only) ------------------------------------------------- */
+
+/* Creates a context for HIP device `device` (checks that it is a gfx950 part).
+ * Errors: MOE_ERR_INVALID_ARG (out == NULL), MOE_ERR_HIP (no such device / not gfx950). */
+int moe_create(moe_ctx **out, int device);
+int moe_destroy(moe_ctx *ctx);
+
+/* Static, never NULL. */
+const char *moe_status_string(int status);
+/* Name of the last HIP error seen by `ctx` ("" if none); valid until the next call on ctx. */
+const char *moe_last_hip_error(const moe_ctx *ctx);
+
+/* MOE_OK if `desc` is a shape the kernels support (the limits above), else
+ * MOE_ERR_INVALID_ARG.  Needs no device. */
+int moe_validate_desc(const moe_layer_desc *desc);
+
+/* Sizes of the packed weight blobs of one expert (0 if desc is invalid). */
+size_t moe_bf16_expert_bytes(const moe_layer_desc *desc);
+size_t moe_int4_expert_q_bytes(const moe_layer_desc *desc);
+size_t moe_int4_expert_sz_bytes(const moe_layer_desc *desc);
+
+/* Bytes of device workspace that moe_draft_layer_int4 / moe_verify_layer_bf16 need for up to
+ * `max_tokens` tokens per call (256-byte aligned base).  Contents need no initialisation and
+ * carry nothing from call to call. */
+int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *bytes);
+
+/* ---- router: softmax + top-k, histogram, permutation --------------------------------- */
+
+/*
+ * Section 2.1 (a router yields a distribution over the experts and the top-k are selected,
+ * their outputs weighted by the router scores), section 3.3.1 (each lookahead entry is an
+ * expert id with a confidence score from the gating logits), section 3.4.4 (tokens of one
+ * expert are made contiguous before verification).
+ *
+ *   l[t,e] = sum_h x[t,h] w_router[e,h] (+ router_bias[e]),  accumulated in fp64
+ *   topk_ids[t,:]  = the k largest logits of token t, descending; equal logits -> lower
+ *                    expert index first
+ *   topk_conf[t,j] = softmax(l[t,:])[topk_ids[t,j]]
+ *   topk_w[t,j]    = topk_conf[t,j] / sum_j topk_conf[t,j] if desc->renormalize else topk_conf
+ *   counts[e]      = number of assignments a with topk_ids[a] == e
+ *   offsets        = exclusive prefix sum of counts, offsets[E] = T * k
+ *   perm           = assignment indices sorted by expert, ascending a inside one expert
+ *
+ * x [T,H] bf16 row-major; w_router [E,H] bf16 row-major; router_bias [E] fp32 or NULL.
+ * topk_ids [T,k] int32 and topk_w [T,k] fp32 are required; topk_conf [T,k] fp32, counts [E],
+ * offsets [E+1], perm [T*k] (int32) may each be NULL (counts/offsets/perm: all or none).
+ * Pointers 16-byte aligned (x, w_router) / 4-byte aligned (the rest).
+ */
+int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
+                   const void *x_bf16, const void *w_router_bf16, const float *router_bias,
+                   int T,
+                   int32_t *topk_ids, float *topk_w, float *topk_conf,
+                   int32_t *counts, int32_t *offsets, int32_t *perm,
+                   void *stream);
+
+/* ---- draft pass ----------------------------------------------------------------------- */
+
+/*
+ * Section 3.4.2-3.4.3: the draft model keeps the gate and the shared experts in 16 bit and
+ * runs every routed expert from 4-bit group-quantised weights in one fused pass; section
+ * 3.3.1: it records (expert id, confidence) per token and layer for the lookahead buffer.
+ *
+ *   route as in moe_route_topk, then
+ *   y[t] = sum_j w[t,j] FFN_{ids[t,j]}(x[t]) + sum_s FFN_shared_s(x[t])
+ *   FFN(x) = Wd ( silu(Wg x) (.) (Wu x) ),  routed experts with W = (q - z) * s,
+ *   products accumulated in fp32, the intermediate kept in more than fp16 precision,
+ *   y written as fp32.
+ *
+ * routed: the E int4 experts (struct above).  shared_bf16: S contiguous bf16 expert blobs, or
+ * NULL when desc->n_shared == 0.  1 <= T <= MOE_MAX_DRAFT_TOKENS (the canonical call is
+ * T = 1; with T > 1 each distinct expert's weights are still streamed once).
+ * y_f32 [T,H]; ids_out [T,k] int32 in rank order; conf_out [T,k] fp32 or NULL.  ids_out /
+ * conf_out may point into a larger [step, layer, T, k] buffer so that a whole window can be
+ * copied to the host at once (section 4.1.2, batched device-to-host transfer).
+ * Activations must satisfy |x| < 2^100 and the SwiGLU intermediate |h| < 65504.
+ */
+int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
+                         const void *x_bf16, const void *w_router_bf16,
+                         const float *router_bias,
+                         const moe_int4_experts *routed, const void *shared_bf16,
+                         int T,
+                         float *y_f32, int32_t *ids_out, float *conf_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- union of the experts of a speculative window -------------------------------------- */
+
+/*
+ * Section 2.3: verification must load and compute the union of the experts of all tokens of
+ * the window; section 3.2.2: the experts still to be fetched, E_new, are that union minus
+ * the cache contents.
+ *
+ * ids [n_ids] int32 (any shape flattened, values in [0, n_experts)), n_ids >= 0.
+ * slot_of_expert [n_experts] int32 (-1 = not resident) or NULL.
+ * mask [ceil(n_experts / 64)] uint64: bit e set iff e occurs.  list [n_experts]: the
+ * distinct ids ascending (first *n_list entries valid).  missing [n_experts] / n_missing:
+ * the listed experts whose slot is negative, ascending; with slot_of_expert == NULL
+ * *n_missing = 0 and `missing` may be NULL.  All outputs are device memory.
+ */
+int moe_expert_union(moe_ctx *ctx, const int32_t *ids, int n_ids, int n_experts,
+                     const int32_t *slot_of_expert,
+                     uint64_t *mask, int32_t *list, int32_t *n_list,
+                     int32_t *missing, int32_t *n_missing, void *stream);
+
+/* ---- verify pass ------------------------------------------------------------------------ */
+
+/*
+ * Section 3.4.4 and section 2.3: the target model's MoE layer over the K+1 tokens of the
+ * window in 16 bit, tokens regrouped per expert so that every distinct expert's weights are
+ * streamed once, experts read from the VRAM expert cache.
+ *
+ *   route as in moe_route_topk, then y as in the draft pass with bf16 weights, fp32
+ *   accumulation, the SwiGLU intermediate rounded to bf16, y rounded to bf16.
+ *
+ * Expert e lives at slot_pool + slot_of_expert[e] * slot_stride_bytes as one bf16 expert
+ * blob; slot_of_expert[e] < 0 means "not resident".  Without flags, the terms of non-resident
+ * experts are left out of y and their ids are written to missing[0 .. *n_missing) ascending
+ * (the caller fetches them and calls again with MOE_VERIFY_ACCUMULATE |
+ * MOE_VERIFY_ONLY_LISTED and the same `missing` / `n_missing`, which then adds exactly those
+ * terms -- the on-demand load of section 4.1.2).  With MOE_VERIFY_ONLY_LISTED the shared
+ * experts are skipped (the first call already added them) and `missing` / `n_missing` are
+ * read, then rewritten with what is still absent.
+ * MOE_VERIFY_STRICT: the call waits for the stream and returns MOE_ERR_MISSING_EXPERT if
+ * *n_missing != 0 (y is then still the partial sum).
+ *
+ * 1 <= T <= MOE_MAX_TOKENS.  y_bf16 [T,H]; ids_out [T,k] int32 or NULL; missing [E] int32 and
+ * n_missing [1] int32 device memory, required.
+ */
+int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
+                          const void *x_bf16, const void *w_router_bf16,
+                          const float *router_bias,
+                          const void *slot_pool, size_t slot_stride_bytes,
+                          const int32_t *slot_of_expert, const void *shared_bf16,
+                          int T, int flags,
+                          void *y_bf16, int32_t *ids_out,
+                          int32_t *missing, int32_t *n_missing,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- expert fetch ------------------------------------------------------------------------ */
+
+/*
+ * Section 4.1.2: experts are loaded asynchronously from pinned host memory with non-blocking
+ * copies on their own stream, ordered against compute with events.
+ *
+ * Copies `bytes` from src_pinned_host (HOST pointer, page-locked) to dst_slot_dev on
+ * copy_stream and, if done_event is not NULL, records it on copy_stream after the copy.
+ * The compute stream must wait on that event before a verify call reads the slot.
+ */
+int moe_expert_copy_async(moe_ctx *ctx, void *dst_slot_dev, const void *src_pinned_host,
+                          size_t bytes, void *copy_stream, void *done_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOESPEQ_H */

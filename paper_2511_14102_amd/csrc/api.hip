@@ -1,0 +1,291 @@
+// Host side of the C ABI declared in include/moespeq.h: argument validation, workspace
+// carve-up and kernel sequencing.  No device memory is allocated here and no call waits for
+// the device (except the documented MOE_VERIFY_STRICT mode).
+#include <string.h>
+#include <new>
+#include "plan.h"
+
+struct moe_ctx {
+    int device;
+    int n_cu;
+    char arch[64];
+    char hip_error[128];
+};
+
+namespace moespeq {
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+WsLayout ws_layout(const moe_layer_desc &d, int T)
+{
+    WsLayout L;
+    const size_t n = (size_t)T * d.top_k, rows = n + (size_t)T * d.n_shared;
+    size_t o = 0;
+    L.plan = o; o += align256(sizeof(Plan));
+    L.xh = o;   o += align256((size_t)T * d.hidden * 2);
+    L.hh = o;   o += align256(n * d.inter * 2);
+    L.hl = o;   o += align256(n * d.inter * 2);
+    L.hb = o;   o += align256(rows * d.inter * 2);
+    L.obuf = o; o += align256(rows * d.hidden * 4);
+    L.part = o; o += align256((size_t)kDraftDownSplit * n * d.hidden * 4);
+    L.total = o;
+    return L;
+}
+
+static bool aligned(const void *p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+static int check_desc(const moe_layer_desc *d)
+{
+    if (!d) return MOE_ERR_INVALID_ARG;
+    if (d->hidden < 64 || d->hidden % 64 || d->inter < 64 || d->inter % 64) return MOE_ERR_INVALID_ARG;
+    if (d->hidden > (1 << 16) || d->inter > (1 << 17)) return MOE_ERR_INVALID_ARG;
+    if (d->n_experts < 1 || d->n_experts > MOE_MAX_EXPERTS) return MOE_ERR_INVALID_ARG;
+    if (d->top_k < 1 || d->top_k > MOE_MAX_TOPK || d->top_k > d->n_experts) return MOE_ERR_INVALID_ARG;
+    if (d->n_shared < 0 || d->n_shared > MOE_MAX_SHARED) return MOE_ERR_INVALID_ARG;
+    const int g = d->group_size;
+    if (g != 32 && g != 64 && g != 128) return MOE_ERR_INVALID_ARG;
+    if (d->hidden % g || d->inter % g) return MOE_ERR_INVALID_ARG;
+    return MOE_OK;
+}
+
+static int check_tokens(const moe_layer_desc *d, int T, int maxT)
+{
+    if (T < 1 || T > maxT || T * d->top_k > MOE_MAX_ASSIGN) return MOE_ERR_INVALID_ARG;
+    return MOE_OK;
+}
+
+static Shape make_shape(const moe_layer_desc *d, int T)
+{
+    Shape s;
+    s.T = T; s.H = d->hidden; s.E = d->n_experts; s.I = d->inter; s.k = d->top_k;
+    s.S = d->n_shared; s.g = d->group_size; s.renorm = d->renormalize ? 1 : 0;
+    return s;
+}
+
+static int hip_status(moe_ctx *ctx, hipError_t e)
+{
+    if (e == hipSuccess) return MOE_OK;
+    if (ctx) {
+        strncpy(ctx->hip_error, hipGetErrorName(e), sizeof(ctx->hip_error) - 1);
+        ctx->hip_error[sizeof(ctx->hip_error) - 1] = 0;
+    }
+    return MOE_ERR_HIP;
+}
+
+}  // namespace moespeq
+
+using namespace moespeq;
+
+extern "C" {
+
+int moe_create(moe_ctx **out, int device)
+{
+    if (!out) return MOE_ERR_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return MOE_ERR_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return MOE_ERR_HIP;
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return MOE_ERR_HIP;   // kernels are gfx950 only
+    moe_ctx *c = new (std::nothrow) moe_ctx;
+    if (!c) return MOE_ERR_HIP;
+    memset(c, 0, sizeof *c);
+    c->device = device;
+    c->n_cu = prop.multiProcessorCount;
+    strncpy(c->arch, prop.gcnArchName, sizeof(c->arch) - 1);
+    *out = c;
+    return MOE_OK;
+}
+
+int moe_destroy(moe_ctx *ctx)
+{
+    delete ctx;
+    return MOE_OK;
+}
+
+const char *moe_status_string(int status)
+{
+    switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_INVALID_ARG: return "invalid argument";
+    case MOE_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case MOE_ERR_HIP: return "HIP error";
+    case MOE_ERR_MISSING_EXPERT: return "an expert needed by the call is not resident";
+    default: return "unknown status";
+    }
+}
+
+const char *moe_last_hip_error(const moe_ctx *ctx) { return ctx ? ctx->hip_error : ""; }
+
+int moe_validate_desc(const moe_layer_desc *desc) { return check_desc(desc); }
+
+size_t moe_bf16_expert_bytes(const moe_layer_desc *d)
+{
+    if (check_desc(d) != MOE_OK) return 0;
+    return (size_t)3 * d->hidden * d->inter * 2;
+}
+
+size_t moe_int4_expert_q_bytes(const moe_layer_desc *d)
+{
+    if (check_desc(d) != MOE_OK) return 0;
+    return (size_t)3 * d->hidden * d->inter / 2;
+}
+
+size_t moe_int4_expert_sz_bytes(const moe_layer_desc *d)
+{
+    if (check_desc(d) != MOE_OK) return 0;
+    return (size_t)3 * d->hidden * d->inter / d->group_size * 4;
+}
+
+int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *bytes)
+{
+    if (!bytes || check_desc(desc) != MOE_OK) return MOE_ERR_INVALID_ARG;
+    if (check_tokens(desc, max_tokens, MOE_MAX_TOKENS) != MOE_OK) return MOE_ERR_INVALID_ARG;
+    *bytes = ws_layout(*desc, max_tokens).total;
+    return MOE_OK;
+}
+
+int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
+                   const void *x, const void *wr, const float *bias, int T,
+                   int32_t *ids, float *w, float *conf,
+                   int32_t *counts, int32_t *offsets, int32_t *perm, void *stream)
+{
+    if (!ctx || check_desc(desc) != MOE_OK || check_tokens(desc, T, MOE_MAX_TOKENS) != MOE_OK)
+        return MOE_ERR_INVALID_ARG;
+    if (!x || !wr || !ids || !w || !aligned(x, 16) || !aligned(wr, 16) || !aligned(ids, 4) ||
+        !aligned(w, 4) || !aligned(conf, 4) || !aligned(bias, 4))
+        return MOE_ERR_INVALID_ARG;
+    const int nperm = (counts != nullptr) + (offsets != nullptr) + (perm != nullptr);
+    if (nperm != 0 && nperm != 3) return MOE_ERR_INVALID_ARG;
+    if (!aligned(counts, 4) || !aligned(offsets, 4) || !aligned(perm, 4)) return MOE_ERR_INVALID_ARG;
+    const Shape s = make_shape(desc, T);
+    hipStream_t st = (hipStream_t)stream;
+    launch_route(s, x, wr, bias, ids, w, conf, nullptr, nullptr, st);
+    if (nperm) launch_perm(s, ids, counts, offsets, perm, st);
+    return hip_status(ctx, hipGetLastError());
+}
+
+int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
+                         const void *x, const void *wr, const float *bias,
+                         const moe_int4_experts *routed, const void *shared, int T,
+                         float *y, int32_t *ids_out, float *conf_out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || check_desc(desc) != MOE_OK || check_tokens(desc, T, MOE_MAX_DRAFT_TOKENS) != MOE_OK)
+        return MOE_ERR_INVALID_ARG;
+    if (!x || !wr || !routed || !routed->q || !routed->sz || !y || !ids_out)
+        return MOE_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(wr, 16) || !aligned(bias, 4) || !aligned(routed->q, 16) ||
+        !aligned(routed->sz, 16) || routed->expert_stride_q % 16 || routed->expert_stride_sz % 16 ||
+        !aligned(y, 16) || !aligned(ids_out, 4) || !aligned(conf_out, 4) || !aligned(shared, 16))
+        return MOE_ERR_INVALID_ARG;
+    if (routed->expert_stride_q < moe_int4_expert_q_bytes(desc) ||
+        routed->expert_stride_sz < moe_int4_expert_sz_bytes(desc))
+        return MOE_ERR_INVALID_ARG;
+    if (desc->n_shared > 0 && !shared) return MOE_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(*desc, T);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+
+    const Shape s = make_shape(desc, T);
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    Plan *plan = (Plan *)(ws + L.plan);
+    launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, ws + L.xh, plan->x_unscale, st);
+    PlanArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = plan; a.mode = 0;
+    a.w0 = routed->q; a.stride0 = routed->expert_stride_q;
+    a.w1 = routed->sz; a.stride1 = routed->expert_stride_sz;
+    a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
+    a.ids_out = ids_out; a.conf_out = conf_out;
+    launch_plan(s, a, st);
+    launch_draft_gateup(s, plan, ws + L.xh, ws + L.hh, ws + L.hl, st);
+    launch_draft_down(s, plan, ws + L.hh, ws + L.hl, (float *)(ws + L.part), st);
+    if (s.S > 0) {   // shared experts stay 16-bit in the draft model (section 3.4.2)
+        launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, st);
+        launch_bf16_down(s, plan, 0, s.S, ws + L.hb, (float *)(ws + L.obuf), st);
+    }
+    launch_combine(s, plan, (const float *)(ws + L.part), kDraftDownSplit,
+                   (const float *)(ws + L.obuf), 0, 0, y, st);
+    return hip_status(ctx, hipGetLastError());
+}
+
+int moe_expert_union(moe_ctx *ctx, const int32_t *ids, int n_ids, int n_experts,
+                     const int32_t *slot_of_expert, uint64_t *mask, int32_t *list, int32_t *n_list,
+                     int32_t *missing, int32_t *n_missing, void *stream)
+{
+    if (!ctx || n_ids < 0 || n_experts < 1 || n_experts > MOE_MAX_EXPERTS) return MOE_ERR_INVALID_ARG;
+    if ((n_ids > 0 && !ids) || !mask || !list || !n_list || !n_missing) return MOE_ERR_INVALID_ARG;
+    if (slot_of_expert && !missing) return MOE_ERR_INVALID_ARG;
+    if (!aligned(ids, 4) || !aligned(slot_of_expert, 4) || !aligned(mask, 8) || !aligned(list, 4) ||
+        !aligned(n_list, 4) || !aligned(missing, 4) || !aligned(n_missing, 4))
+        return MOE_ERR_INVALID_ARG;
+    launch_union(ids, n_ids, n_experts, slot_of_expert, mask, list, n_list, missing, n_missing,
+                 (hipStream_t)stream);
+    return hip_status(ctx, hipGetLastError());
+}
+
+int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
+                          const void *x, const void *wr, const float *bias,
+                          const void *slot_pool, size_t slot_stride, const int32_t *slot_of_expert,
+                          const void *shared, int T, int flags,
+                          void *y, int32_t *ids_out, int32_t *missing, int32_t *n_missing,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || check_desc(desc) != MOE_OK || check_tokens(desc, T, MOE_MAX_TOKENS) != MOE_OK)
+        return MOE_ERR_INVALID_ARG;
+    if (flags & ~(MOE_VERIFY_ACCUMULATE | MOE_VERIFY_ONLY_LISTED | MOE_VERIFY_STRICT))
+        return MOE_ERR_INVALID_ARG;
+    if (!x || !wr || !slot_pool || !slot_of_expert || !y || !missing || !n_missing)
+        return MOE_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(wr, 16) || !aligned(bias, 4) || !aligned(slot_pool, 16) ||
+        slot_stride % 16 || slot_stride < moe_bf16_expert_bytes(desc) || !aligned(slot_of_expert, 4) ||
+        !aligned(shared, 16) || !aligned(y, 8) || !aligned(ids_out, 4) || !aligned(missing, 4) ||
+        !aligned(n_missing, 4))
+        return MOE_ERR_INVALID_ARG;
+    if (desc->n_shared > 0 && !shared) return MOE_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(*desc, T);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+
+    const Shape s = make_shape(desc, T);
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    Plan *plan = (Plan *)(ws + L.plan);
+    launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, nullptr, nullptr, st);
+    PlanArgs a;
+    memset(&a, 0, sizeof a);
+    a.plan = plan; a.mode = 1;
+    a.w0 = slot_pool; a.stride0 = slot_stride;
+    a.slot_of_expert = slot_of_expert;
+    a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
+    a.flags = flags;
+    a.ids_out = ids_out;
+    a.missing = missing; a.n_missing = n_missing;
+    launch_plan(s, a, st);
+    const int nexp = s.S + (s.E < s.T * s.k ? s.E : s.T * s.k);
+    launch_bf16_gateup(s, plan, 0, nexp, x, ws + L.hb, st);
+    launch_bf16_down(s, plan, 0, nexp, ws + L.hb, (float *)(ws + L.obuf), st);
+    launch_combine(s, plan, (const float *)(ws + L.obuf), 1, (const float *)(ws + L.obuf),
+                   (flags & MOE_VERIFY_ACCUMULATE) ? 1 : 0, 1, y, st);
+    int rc = hip_status(ctx, hipGetLastError());
+    if (rc != MOE_OK) return rc;
+    if (flags & MOE_VERIFY_STRICT) {
+        int32_t nm = 0;
+        hipError_t e = hipMemcpyAsync(&nm, n_missing, sizeof nm, hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) return hip_status(ctx, e);
+        if (nm != 0) return MOE_ERR_MISSING_EXPERT;
+    }
+    return MOE_OK;
+}
+
+int moe_expert_copy_async(moe_ctx *ctx, void *dst, const void *src, size_t bytes,
+                          void *copy_stream, void *done_event)
+{
+    if (!ctx || !dst || !src || bytes == 0) return MOE_ERR_INVALID_ARG;
+    hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, (hipStream_t)copy_stream);
+    if (e == hipSuccess && done_event) e = hipEventRecord((hipEvent_t)done_event, (hipStream_t)copy_stream);
+    return hip_status(ctx, e);
+}
+
+}  // extern "C"

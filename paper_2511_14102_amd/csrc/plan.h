@@ -1,0 +1,90 @@
+// Internal: the per-call execution plan that the route/plan kernels leave in the workspace
+// and that the expert kernels read, plus the host-side launcher prototypes of each .hip file.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/moespeq.h"
+
+namespace moespeq {
+
+constexpr int kMaxRows = MOE_MAX_ASSIGN + MOE_MAX_TOKENS * MOE_MAX_SHARED;   // routed + shared rows
+constexpr int kMaxActive = MOE_MAX_ASSIGN + MOE_MAX_SHARED;                   // distinct experts per call
+
+// A "row" is one (token, expert) pair the expert kernels work on.  Rows of one expert are
+// contiguous: routed rows are the stable permutation of the assignments (section 3.4.4),
+// shared-expert rows follow, one per token and shared expert.
+struct Plan {
+    int32_t n_active;                 // experts the expert kernels run (routed present + shared)
+    int32_t n_routed_active;
+    int32_t n_rows;                   // T*k + T*S
+    int32_t n_missing;
+    int32_t ids[MOE_MAX_ASSIGN];      // [T,k]
+    float   w[MOE_MAX_ASSIGN];
+    float   conf[MOE_MAX_ASSIGN];
+    int32_t count[MOE_MAX_EXPERTS];
+    int32_t off[MOE_MAX_EXPERTS + 1];
+    int32_t perm[MOE_MAX_ASSIGN];
+    int32_t act_expert[kMaxActive];   // expert id (>= E: shared expert id - E)
+    int32_t act_off[kMaxActive];      // first row
+    int32_t act_cnt[kMaxActive];      // number of rows (tokens of that expert)
+    uint64_t act_w0[kMaxActive];      // weights: bf16 blob / int4 codes blob
+    uint64_t act_w1[kMaxActive];      // int4 scale-zero blob
+    int32_t row_tok[kMaxRows];        // token of a row
+    float   row_w[kMaxRows];          // routing weight of a row (1 for shared)
+    int32_t row_live[kMaxRows];       // 0: expert absent, the row's output must be skipped
+    float   x_unscale[MOE_MAX_TOKENS];   // draft: 1 / (power-of-two scale applied to x)
+};
+
+struct Shape {
+    int T, H, E, I, k, S, g, renorm;
+};
+
+// Workspace carve-up (byte offsets from a 256-byte aligned base).
+struct WsLayout {
+    size_t plan, xh, hh, hl, hb, obuf, part, total;   // xh: fp16 x; hh/hl: fp16 hi/lo of h; hb: bf16 h
+};
+WsLayout ws_layout(const moe_layer_desc &d, int max_tokens);
+
+constexpr int kDraftDownSplit = 4;    // K-splits across workgroups in the int4 down kernel
+
+// route.hip
+// xh / x_unscale: optional fp16 copy of x scaled by a power of two per token (draft operand)
+void launch_route(const Shape &s, const void *x, const void *wr, const float *bias,
+                  int32_t *ids, float *w, float *conf, void *xh, float *x_unscale,
+                  hipStream_t st);
+void launch_perm(const Shape &s, const int32_t *ids, int32_t *count, int32_t *off,
+                 int32_t *perm, hipStream_t st);
+struct PlanArgs {
+    Plan *plan;
+    int mode;                          // 0 draft (int4 routed, all present), 1 verify (slot table)
+    const void *w0; size_t stride0;    // draft: codes base / stride; verify: slot pool / stride
+    const void *w1; size_t stride1;    // draft: scale-zero base / stride
+    const int32_t *slot_of_expert;
+    const void *shared; size_t shared_stride;
+    int flags;
+    int32_t *ids_out; float *conf_out;
+    int32_t *missing; int32_t *n_missing;
+};
+void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st);
+void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
+                  uint64_t *mask, int32_t *list, int32_t *n_list,
+                  int32_t *missing, int32_t *n_missing, hipStream_t st);
+
+// draft_int4.hip
+void launch_draft_gateup(const Shape &s, const Plan *plan, const void *xh, void *hh, void *hl,
+                         hipStream_t st);
+void launch_draft_down(const Shape &s, const Plan *plan, const void *hh, const void *hl,
+                       float *part, hipStream_t st);
+
+// expert_bf16.hip
+void launch_bf16_gateup(const Shape &s, const Plan *plan, int first_active, int n_active_max,
+                        const void *x, void *hb, hipStream_t st);
+void launch_bf16_down(const Shape &s, const Plan *plan, int first_active, int n_active_max,
+                      const void *hb, float *obuf, hipStream_t st);
+// y[t] = (accumulate ? y[t] : 0) + sum over the token's live routed rows of
+// sum_{split < nsplit} routed[split][row] + sum over its live shared rows of obuf[row];
+// routed is [nsplit][T*k][H] fp32, obuf is [rows][H] fp32 indexed by row number.
+void launch_combine(const Shape &s, const Plan *plan, const float *routed, int nsplit,
+                    const float *obuf, int accumulate, int out_bf16, void *y, hipStream_t st);
+
+}  // namespace moespeq

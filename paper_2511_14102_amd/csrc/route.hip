@@ -1,0 +1,341 @@
+// Router, top-k, softmax weights, token->expert histogram / permutation, execution plan and
+// expert union kernels (gfx950).
+//
+// Paper section 2.1: the router turns a token's hidden state into a distribution over the
+// experts and the top-k experts are selected, weighted by their scores.  Section 3.4.2: the
+// gate stays 16-bit in the draft model because routing errors corrupt the lookahead, so the
+// logits here are accumulated in fp64 (products of two bf16 values are exact), which keeps
+// the selected ids identical to an exact evaluation unless two logits agree to ~1e-13.
+// Section 3.4.4: assignments are regrouped per expert.  Section 2.3 / 3.2.2: union of the
+// experts of a window and the part of it that is not resident.
+#include "plan.h"
+
+namespace moespeq {
+
+namespace {
+
+constexpr int kRouteThreads = 1024;
+
+__device__ inline double bf16_to_f64(uint16_t b) {
+    return (double)__uint_as_float((uint32_t)b << 16);
+}
+
+__device__ inline double wave_sum_f64(double v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+__device__ inline double wave_max_f64(double v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmax(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+// One workgroup per token: logits of all experts (one wave per expert row at a time), then
+// wave 0 selects the top k and computes the softmax weights.  Optionally also writes the
+// token's activations as fp16 scaled by a power of two (draft pass operand).
+__global__ __launch_bounds__(kRouteThreads)
+void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
+                  const float *__restrict__ bias, int H, int E, int k, int renorm,
+                  int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf,
+                  _Float16 *__restrict__ xh, float *__restrict__ x_unscale)
+{
+    __shared__ double s_logit[MOE_MAX_EXPERTS];
+    __shared__ float s_amax[kRouteThreads / 64];
+    const int t = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nwave = kRouteThreads / 64;
+    const uint16_t *xt = x + (size_t)t * H;
+    const int chunks = H / 8;
+
+    for (int e = wave; e < E; e += nwave) {
+        const uint16_t *row = wr + (size_t)e * H;
+        double acc = 0.0;
+        for (int c = lane; c < chunks; c += 64) {
+            uint4 xv = *reinterpret_cast<const uint4 *>(xt + c * 8);
+            uint4 wv = *reinterpret_cast<const uint4 *>(row + c * 8);
+            const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w};
+            const uint32_t ws[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc = fma(bf16_to_f64((uint16_t)(xs[i] & 0xffff)), bf16_to_f64((uint16_t)(ws[i] & 0xffff)), acc);
+                acc = fma(bf16_to_f64((uint16_t)(xs[i] >> 16)), bf16_to_f64((uint16_t)(ws[i] >> 16)), acc);
+            }
+        }
+        acc = wave_sum_f64(acc);
+        if (lane == 0) s_logit[e] = acc + (bias ? (double)bias[e] : 0.0);
+    }
+
+    if (xh) {   // power-of-two scaled fp16 copy of the activations
+        float amax = 0.f;
+        for (int h = threadIdx.x; h < H; h += kRouteThreads)
+            amax = fmaxf(amax, fabsf(__uint_as_float((uint32_t)xt[h] << 16)));
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+        if (lane == 0) s_amax[wave] = amax;
+    }
+    __syncthreads();
+    if (xh) {
+        float amax = 0.f;
+        for (int i = 0; i < nwave; ++i) amax = fmaxf(amax, s_amax[i]);
+        int sh = 0;                                   // scale = 2^sh puts amax in [2^14, 2^15)
+        if (amax > 0.f) {
+            int ex;
+            (void)frexpf(amax, &ex);                  // amax = m * 2^ex, m in [0.5, 1)
+            sh = 15 - ex;
+            sh = sh > 100 ? 100 : (sh < -100 ? -100 : sh);
+        }
+        const float scale = ldexpf(1.f, sh);
+        for (int h = threadIdx.x; h < H; h += kRouteThreads)
+            xh[(size_t)t * H + h] = (_Float16)(__uint_as_float((uint32_t)xt[h] << 16) * scale);
+        if (threadIdx.x == 0) x_unscale[t] = ldexpf(1.f, -sh);
+    }
+
+    if (wave != 0) return;
+    // each lane owns logits lane, lane + 64, lane + 128, lane + 192
+    double l[4];
+    double mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int e = lane + 64 * i;
+        l[i] = e < E ? s_logit[e] : -INFINITY;
+        mx = fmax(mx, l[i]);
+    }
+    mx = wave_max_f64(mx);
+    double den = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (lane + 64 * i < E) den += exp(l[i] - mx);
+    den = wave_sum_f64(den);
+
+    unsigned taken = 0;
+    double sel_sum = 0.0;
+    double my_conf = 0.0;      // lane j keeps the j-th confidence
+    int my_id = 0;
+    for (int j = 0; j < k; ++j) {
+        double bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int e = lane + 64 * i;
+            if (e < E && !((taken >> i) & 1) && (bi == 0x7fffffff || l[i] > bv)) { bv = l[i]; bi = e; }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            double ov = __shfl_xor(bv, m, 64);
+            int oi = __shfl_xor(bi, m, 64);
+            if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+        }
+        if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+        double p = exp(bv - mx) / den;
+        sel_sum += p;
+        if (lane == j) { my_conf = p; my_id = bi; }
+    }
+    if (lane < k) {
+        ids[(size_t)t * k + lane] = my_id;
+        float c = (float)my_conf;
+        if (conf) conf[(size_t)t * k + lane] = c;
+        w[(size_t)t * k + lane] = renorm ? (float)(my_conf / sel_sum) : c;
+    }
+}
+
+// count / off / perm for n assignments over E experts; one workgroup, results in `count`,
+// `off`, `perm` (global or shared memory).  Thread e owns expert e.
+__device__ inline void histogram_perm(const int32_t *ids, int n, int E, int32_t *count,
+                                      int32_t *off, int32_t *perm, int32_t *s_count)
+{
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        int c = 0;
+        for (int a = 0; a < n; ++a) c += (ids[a] == e);
+        s_count[e] = c;
+        count[e] = c;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e <= E; e += blockDim.x) {
+        int o = 0;
+        for (int i = 0; i < e; ++i) o += s_count[i];
+        off[e] = o;
+        if (e < E) {
+            int p = o;
+            for (int a = 0; a < n; ++a)
+                if (ids[a] == e) perm[p++] = a;     // ascending a: stable
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256)
+void perm_kernel(const int32_t *__restrict__ ids, int n, int E, int32_t *count, int32_t *off,
+                 int32_t *perm)
+{
+    __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
+    __shared__ int32_t s_count[MOE_MAX_EXPERTS];
+    for (int a = threadIdx.x; a < n; a += blockDim.x) s_ids[a] = ids[a];
+    __syncthreads();
+    histogram_perm(s_ids, n, E, count, off, perm, s_count);
+}
+
+// Builds the execution plan: histogram / permutation, the list of experts to run (shared
+// experts at active indices [0, S), then present routed experts ascending), their weight
+// pointers and row ranges, the per-row token / weight / live flags, and the missing list.
+__global__ __launch_bounds__(256)
+void plan_kernel(Plan *__restrict__ plan, int T, int E, int k, int S, int mode,
+                 const char *w0, size_t stride0, const char *w1, size_t stride1,
+                 const int32_t *__restrict__ slot_of_expert,
+                 const char *shared, size_t shared_stride, int flags,
+                 int32_t *ids_out, float *conf_out, int32_t *missing, int32_t *n_missing)
+{
+    __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
+    __shared__ int32_t s_count[MOE_MAX_EXPERTS];
+    __shared__ int32_t s_slot[MOE_MAX_EXPERTS];
+    __shared__ unsigned char s_listed[MOE_MAX_EXPERTS];
+    __shared__ int32_t s_nact, s_nmiss;
+    const int n = T * k;
+    const bool only_listed = (flags & MOE_VERIFY_ONLY_LISTED) != 0;
+
+    for (int a = threadIdx.x; a < n; a += blockDim.x) {
+        int id = plan->ids[a];
+        s_ids[a] = id;
+        if (ids_out) ids_out[a] = id;
+        if (conf_out) conf_out[a] = plan->conf[a];
+    }
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        s_slot[e] = mode == 0 ? e : slot_of_expert[e];
+        s_listed[e] = only_listed ? 0 : 1;
+    }
+    __syncthreads();
+    if (only_listed) {
+        int nin = *n_missing;
+        nin = nin < 0 ? 0 : (nin > E ? E : nin);
+        for (int i = threadIdx.x; i < nin; i += blockDim.x) {
+            int e = missing[i];
+            if (e >= 0 && e < E) s_listed[e] = 1;
+        }
+    }
+    __syncthreads();
+    histogram_perm(s_ids, n, E, plan->count, plan->off, plan->perm, s_count);
+
+    // shared experts: active slots [0, S), rows T*k + s*T + t
+    for (int i = threadIdx.x; i < S * T; i += blockDim.x) {
+        plan->row_tok[n + i] = i % T;
+        plan->row_w[n + i] = 1.f;
+        plan->row_live[n + i] = only_listed ? 0 : 1;
+    }
+    if ((int)threadIdx.x < S) {
+        int s = threadIdx.x;
+        plan->act_expert[s] = E + s;
+        plan->act_off[s] = n + s * T;
+        plan->act_cnt[s] = only_listed ? 0 : T;
+        plan->act_w0[s] = (uint64_t)(shared + (size_t)s * shared_stride);
+        plan->act_w1[s] = 0;
+    }
+    // routed experts: ordered compaction, 64 experts per step, by wave 0
+    if (threadIdx.x < 64) {
+        int nact = S, nmiss = 0;
+        for (int base = 0; base < E; base += 64) {
+            int e = base + threadIdx.x;
+            bool used = e < E && s_count[e] > 0 && s_listed[e];
+            bool present = used && s_slot[e] >= 0;
+            bool absent = used && s_slot[e] < 0;
+            unsigned long long bp = __ballot(present), ba = __ballot(absent);
+            unsigned long long below = (1ull << threadIdx.x) - 1ull;
+            if (present) {
+                int u = nact + __popcll(bp & below);
+                int slot = s_slot[e];
+                plan->act_expert[u] = e;
+                plan->act_off[u] = plan->off[e];
+                plan->act_cnt[u] = s_count[e];
+                plan->act_w0[u] = (uint64_t)(w0 + (size_t)slot * stride0);
+                plan->act_w1[u] = w1 ? (uint64_t)(w1 + (size_t)slot * stride1) : 0;
+            }
+            if (absent) missing[nmiss + __popcll(ba & below)] = e;
+            nact += __popcll(bp);
+            nmiss += __popcll(ba);
+        }
+        if (threadIdx.x == 0) { s_nact = nact; s_nmiss = nmiss; }
+    }
+    __syncthreads();
+    for (int pos = threadIdx.x; pos < n; pos += blockDim.x) {
+        int a = plan->perm[pos];
+        int e = s_ids[a];
+        plan->row_tok[pos] = a / k;
+        plan->row_w[pos] = plan->w[a];
+        plan->row_live[pos] = (s_listed[e] && s_slot[e] >= 0) ? 1 : 0;
+    }
+    if (threadIdx.x == 0) {
+        plan->n_active = s_nact;
+        plan->n_routed_active = s_nact - S;
+        plan->n_rows = n + S * T;
+        plan->n_missing = s_nmiss;
+        if (n_missing) *n_missing = s_nmiss;
+    }
+}
+
+// Union of expert ids: bitmask in shared memory, then ordered compaction by one wave.
+__global__ __launch_bounds__(256)
+void union_kernel(const int32_t *__restrict__ ids, int n_ids, int E,
+                  const int32_t *__restrict__ slot, uint64_t *mask, int32_t *list,
+                  int32_t *n_list, int32_t *missing, int32_t *n_missing)
+{
+    __shared__ unsigned int s_bits[MOE_MAX_EXPERTS / 32];
+    if (threadIdx.x < MOE_MAX_EXPERTS / 32) s_bits[threadIdx.x] = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_ids; i += blockDim.x) {
+        int e = ids[i];
+        if (e >= 0 && e < E) atomicOr(&s_bits[e >> 5], 1u << (e & 31));
+    }
+    __syncthreads();
+    if (threadIdx.x >= 64) return;
+    const int words = (E + 63) / 64;
+    if ((int)threadIdx.x < words)
+        mask[threadIdx.x] = (uint64_t)s_bits[2 * threadIdx.x] | ((uint64_t)s_bits[2 * threadIdx.x + 1] << 32);
+    int nl = 0, nm = 0;
+    for (int base = 0; base < E; base += 64) {
+        int e = base + threadIdx.x;
+        bool in = e < E && ((s_bits[e >> 5] >> (e & 31)) & 1u);
+        bool miss = in && slot && slot[e] < 0;
+        unsigned long long bi = __ballot(in), bm = __ballot(miss);
+        unsigned long long below = (1ull << threadIdx.x) - 1ull;
+        if (in) list[nl + __popcll(bi & below)] = e;
+        if (miss) missing[nm + __popcll(bm & below)] = e;
+        nl += __popcll(bi);
+        nm += __popcll(bm);
+    }
+    if (threadIdx.x == 0) { *n_list = nl; *n_missing = nm; }
+}
+
+}  // namespace
+
+void launch_route(const Shape &s, const void *x, const void *wr, const float *bias,
+                  int32_t *ids, float *w, float *conf, void *xh, float *x_unscale,
+                  hipStream_t st)
+{
+    hipLaunchKernelGGL(route_kernel, dim3(s.T), dim3(kRouteThreads), 0, st,
+                       (const uint16_t *)x, (const uint16_t *)wr, bias, s.H, s.E, s.k, s.renorm,
+                       ids, w, conf, (_Float16 *)xh, x_unscale);
+}
+
+void launch_perm(const Shape &s, const int32_t *ids, int32_t *count, int32_t *off,
+                 int32_t *perm, hipStream_t st)
+{
+    hipLaunchKernelGGL(perm_kernel, dim3(1), dim3(256), 0, st, ids, s.T * s.k, s.E, count, off, perm);
+}
+
+void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st)
+{
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, a.plan, s.T, s.E, s.k, s.S, a.mode,
+                       (const char *)a.w0, a.stride0, (const char *)a.w1, a.stride1,
+                       a.slot_of_expert, (const char *)a.shared, a.shared_stride, a.flags,
+                       a.ids_out, a.conf_out, a.missing, a.n_missing);
+}
+
+void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
+                  uint64_t *mask, int32_t *list, int32_t *n_list,
+                  int32_t *missing, int32_t *n_missing, hipStream_t st)
+{
+    hipLaunchKernelGGL(union_kernel, dim3(1), dim3(256), 0, st, ids, n_ids, E, slot, mask, list,
+                       n_list, missing, n_missing);
+}
+
+}  // namespace moespeq

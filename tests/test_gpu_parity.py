@@ -1,0 +1,312 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the five workloads.
+Integers (ids, histogram, permutation, union, missing lists) must match bit for bit; float
+outputs within max|y - y_oracle| <= tol * rms(y_oracle) with tol = 2e-2 for the bf16 verify
+pass and 1e-3 for the int4 draft pass."""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import oracle as orc
+from tests.common import oracle_arrays, oracle_draft, oracle_verify, rel_err, bf16_exact
+from tests.gpu_common import (TOL_DRAFT, TOL_VERIFY, build_layer, say, to_np,
+                              tokens_with_clear_routing)
+
+pytestmark = pytest.mark.gpu
+
+from paper_2511_14102_amd import binding as B          # noqa: E402
+from paper_2511_14102_amd.harness import DeviceLayer   # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+class Case:
+    """One config on the device plus its oracle-side arrays."""
+
+    def __init__(self, ctx, cfg, layer=0, bias=None, resident=None, n_slots=None):
+        say("building", cfg.name, "layer", layer, "bias", bias)
+        self.cfg = cfg
+        self.L = build_layer(cfg, layer, bias=bias)
+        self.A = oracle_arrays(self.L)
+        self.D = DeviceLayer(ctx, cfg, self.L, max_tokens=max(max(cfg.verify_tokens), 8),
+                             resident=resident, n_slots=n_slots)
+        torch.cuda.synchronize()
+        say("  on device")
+
+
+@pytest.fixture(scope="module", params=[c.name for c in synth.CONFIGS])
+def case(request, ctx):
+    cfg = synth.config_by_name(request.param)
+    c = Case(ctx, cfg)
+    yield c
+    del c
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def check_route(case, x, r, ref_ids, ref_w, ref_conf):
+    cfg = case.cfg
+    assert np.array_equal(to_np(r["ids"]), ref_ids)
+    np.testing.assert_allclose(to_np(r["w"]), ref_w, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(to_np(r["conf"]), ref_conf, rtol=2e-6, atol=1e-12)
+    if r.get("count") is not None:
+        cnt, off, pm = orc.perm(ref_ids, cfg.n_experts)
+        assert np.array_equal(to_np(r["count"]), cnt)
+        assert np.array_equal(to_np(r["off"]), off)
+        assert np.array_equal(to_np(r["perm"]), pm)
+
+
+def test_route_topk(case):
+    cfg = case.cfg
+    for T in sorted(set(cfg.verify_tokens) | {1}):
+        x = tokens_with_clear_routing(cfg, case.A, T, step=T)
+        say("route", cfg.name, "T", T)
+        r = case.D.route(x.cuda())
+        torch.cuda.synchronize()
+        ids, w, conf, _ = orc.route(orc.bits(x), case.A["router"], case.A["bias"], cfg.top_k,
+                                    cfg.renormalize)
+        check_route(case, x, r, ids, w, conf)
+
+
+def test_draft_layer(case):
+    cfg = case.cfg
+    T = max(cfg.verify_tokens)
+    x = tokens_with_clear_routing(cfg, case.A, T, step=10)
+    ref = oracle_draft(case.A, x)
+    # canonical use: one token per call, K+1 calls
+    for t in range(T):
+        say("draft", cfg.name, "token", t)
+        r = case.D.draft(x[t:t + 1].cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"][t:t + 1])
+        np.testing.assert_allclose(to_np(r["conf"]), ref["conf"][t:t + 1], rtol=2e-6)
+        e = rel_err(to_np(r["y"]), ref["y"][t:t + 1])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_DRAFT
+    # several tokens in one call (each distinct expert streamed once)
+    Tm = min(T, 8)
+    say("draft", cfg.name, "T", Tm, "in one call")
+    r = case.D.draft(x[:Tm].cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(r["ids"]), ref["ids"][:Tm])
+    e = rel_err(to_np(r["y"]), ref["y"][:Tm])
+    say("   rel err %.3e" % e)
+    assert e <= TOL_DRAFT
+    # same call again: identical bits
+    r2 = case.D.draft(x[:Tm].cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(r["y"], r2["y"]) and torch.equal(r["ids"], r2["ids"])
+
+
+def test_verify_layer(case):
+    cfg = case.cfg
+    for T in cfg.verify_tokens:
+        x = tokens_with_clear_routing(cfg, case.A, T, step=20 + T)
+        ref = oracle_verify(case.A, x)
+        say("verify", cfg.name, "T", T, "unique experts", len(set(ref["ids"].reshape(-1).tolist())))
+        r = case.D.verify(x.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"])
+        assert int(r["n_missing"].item()) == 0
+        e = rel_err(to_np(r["y"]), ref["y"])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_VERIFY
+        r2 = case.D.verify(x.cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(r["y"], r2["y"])
+
+
+def test_union_of_window(case):
+    cfg = case.cfg
+    E = cfg.n_experts
+    rng = np.random.default_rng(cfg.index)
+    slot = np.where(rng.random(E) < 0.5, np.arange(E), -1).astype(np.int32)
+    saved = case.D.slot_of_expert.clone()
+    case.D.slot_of_expert.copy_(torch.from_numpy(slot))
+    try:
+        for n in (0, 1, 7, cfg.top_k * 8, 5 * cfg.top_k * 8):
+            ids = rng.integers(0, E, n).astype(np.int32)
+            say("union", cfg.name, "n", n)
+            r = case.D.union(torch.from_numpy(ids).cuda())
+            torch.cuda.synchronize()
+            mask, lst, miss = orc.union(ids, E, slot)
+            assert np.array_equal(to_np(r["mask"]).view(np.uint64), mask)
+            nl, nm = int(r["n_list"].item()), int(r["n_missing"].item())
+            assert nl == lst.size and nm == miss.size
+            assert np.array_equal(to_np(r["list"])[:nl], lst)
+            assert np.array_equal(to_np(r["missing"])[:nm], miss)
+            r = case.D.union(torch.from_numpy(ids).cuda(), use_slots=False)
+            torch.cuda.synchronize()
+            assert int(r["n_missing"].item()) == 0 and int(r["n_list"].item()) == lst.size
+    finally:
+        case.D.slot_of_expert.copy_(saved)
+
+
+def test_mixtral_all_tokens_same_experts(case):
+    cfg = case.cfg
+    if cfg.name != "mixtral":
+        pytest.skip("the skew case belongs to the mixtral-shaped workload")
+    saved_bias, saved_A = case.D.bias, case.A["bias"]
+    case.D.bias = synth.skew_bias(cfg).cuda()
+    case.A["bias"] = synth.skew_bias(cfg).numpy()
+    try:
+        x = synth.make_tokens(cfg, 8, step=61)
+        ref = oracle_verify(case.A, x)
+        assert len(set(ref["ids"].reshape(-1).tolist())) == 2
+        say("mixtral skew: verify T=8, 2 distinct experts")
+        r = case.D.verify(x.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"])
+        e = rel_err(to_np(r["y"]), ref["y"])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_VERIFY
+    finally:
+        case.D.bias, case.A["bias"] = saved_bias, saved_A
+
+
+# ---------------------------------------------------------------- special cases (tiny shape)
+
+@pytest.fixture(scope="module")
+def tiny(ctx):
+    return Case(ctx, synth.config_by_name("tiny"))
+
+
+def test_exact_ties_pick_the_lower_index(ctx, tiny):
+    cfg = tiny.cfg
+    L = dict(tiny.L)
+    row = L["router"][2:3]
+    L["router"] = row.repeat(cfg.n_experts, 1).contiguous()          # all logits exactly equal
+    D = DeviceLayer(ctx, cfg, L, max_tokens=4, draft=False, verify=False)
+    x = synth.make_tokens(cfg, 4, step=77)
+    say("ties: duplicate router rows")
+    r = D.route(x.cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(r["ids"]), np.tile(np.arange(cfg.top_k, dtype=np.int32), (4, 1)))
+    np.testing.assert_allclose(to_np(r["w"]), 1.0 / cfg.top_k, rtol=1e-6)
+    # small integers: logits exact on both sides, many ties
+    rng = np.random.default_rng(5)
+    xi = bf16_exact(rng.integers(-2, 3, (4, cfg.hidden)).astype(np.float64))
+    L["router"] = bf16_exact(rng.integers(-1, 2, (cfg.n_experts, cfg.hidden)).astype(np.float64))
+    L["router"][5] = L["router"][1]
+    D = DeviceLayer(ctx, cfg, L, max_tokens=4, draft=False, verify=False)
+    say("ties: small-integer logits")
+    r = D.route(xi.cuda())
+    torch.cuda.synchronize()
+    ids, w, conf, _ = orc.route(orc.bits(xi), orc.bits(L["router"]), None, cfg.top_k, True)
+    assert np.array_equal(to_np(r["ids"]), ids)
+    np.testing.assert_allclose(to_np(r["w"]), w, rtol=2e-6)
+
+
+def test_renormalize_off_and_bias(ctx, tiny):
+    cfg = tiny.cfg
+    L = dict(tiny.L)
+    L["router_bias"] = torch.linspace(-1, 1, cfg.n_experts)
+    D = DeviceLayer(ctx, cfg, L, max_tokens=4)
+    D.desc.renormalize = 0
+    A = oracle_arrays(L)
+    x = synth.make_tokens(cfg, 4, step=31)
+    xb = orc.bits(x)
+    ids, w, conf, _ = orc.route(xb, A["router"], A["bias"], cfg.top_k, False)
+    say("renormalize off + bias: route")
+    r = D.route(x.cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(r["ids"]), ids)
+    np.testing.assert_allclose(to_np(r["w"]), conf, rtol=2e-6)
+    y = orc.layer_bf16(xb, A["gate"], A["up"], A["down"], cfg.n_experts, ids, w)
+    say("renormalize off + bias: verify")
+    rv = D.verify(x.cuda())
+    torch.cuda.synchronize()
+    assert rel_err(to_np(rv["y"]), y) <= TOL_VERIFY
+
+
+def test_missing_experts_and_on_demand_accumulate(ctx, tiny):
+    cfg = tiny.cfg
+    E = cfg.n_experts
+    x = tokens_with_clear_routing(cfg, tiny.A, 4, step=41)
+    ref = oracle_verify(tiny.A, x)
+    used = sorted(set(ref["ids"].reshape(-1).tolist()))
+    absent = used[::2]                                     # every other used expert is not resident
+    resident = [e for e in range(E) if e not in absent]
+    D = DeviceLayer(ctx, cfg, tiny.L, max_tokens=4, resident=resident, n_slots=E, draft=False)
+    present = np.ones(E, np.uint8); present[absent] = 0
+    part = oracle_verify(tiny.A, x, present=present)
+    say("missing: first call, absent", absent)
+    r = D.verify(x.cuda())
+    torch.cuda.synchronize()
+    nm = int(r["n_missing"].item())
+    assert nm == len(absent) and to_np(r["missing"])[:nm].tolist() == absent
+    assert rel_err(to_np(r["y"]), part["y"]) <= TOL_VERIFY
+    # strict mode reports it as an error
+    with pytest.raises(B.MoeError) as ei:
+        D.verify(x.cuda(), flags=B.MOE_VERIFY_STRICT)
+    assert ei.value.status == B.MOE_ERR_MISSING_EXPERT
+    # fetch the missing experts from pinned host memory on a side stream, then add their terms
+    y = r["y"]
+    D.verify(x.cuda(), y=y)                                # recompute the partial sum (strict call overwrote nothing else)
+    copy_stream = torch.cuda.Stream()
+    ev = torch.cuda.Event()
+    ev.record(copy_stream)                                 # torch creates the HIP event on first record
+    from paper_2511_14102_amd import pack
+    for i, e in enumerate(absent):
+        blob = pack.pack_bf16_expert(tiny.L["gate"][e], tiny.L["up"][e], tiny.L["down"][e]).pin_memory()
+        slot = len(resident) + i
+        ctx.expert_copy_async(D.slot_view(slot), blob, blob.numel(), copy_stream, ev)
+        D.set_slot(e, slot)
+    torch.cuda.current_stream().wait_event(ev)
+    say("missing: accumulate call")
+    r2 = D.verify(x.cuda(), flags=B.MOE_VERIFY_ACCUMULATE | B.MOE_VERIFY_ONLY_LISTED, y=y)
+    torch.cuda.synchronize()
+    assert int(r2["n_missing"].item()) == 0
+    assert rel_err(to_np(y), ref["y"]) <= TOL_VERIFY
+    # slot numbering is irrelevant: a fresh layer with all experts in reversed slots agrees
+    D2 = DeviceLayer(ctx, cfg, tiny.L, max_tokens=4, resident=list(range(E))[::-1], draft=False)
+    r3 = D2.verify(x.cuda())
+    torch.cuda.synchronize()
+    assert rel_err(to_np(r3["y"]), ref["y"]) <= TOL_VERIFY
+
+
+def test_argument_errors_enqueue_nothing(ctx, tiny):
+    D = tiny.D
+    x = synth.make_tokens(tiny.cfg, 4).cuda()
+    with pytest.raises(B.MoeError) as ei:                  # misaligned activations
+        bad = torch.empty(4 * 256 + 8, dtype=torch.bfloat16, device="cuda")[1:1 + 4 * 256].view(4, 256)
+        D.route(bad)
+    assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    small = D.workspace
+    D.workspace = small[:1024]
+    try:
+        with pytest.raises(B.MoeError) as ei:
+            D.verify(x)
+        assert ei.value.status == B.MOE_ERR_WORKSPACE
+    finally:
+        D.workspace = small
+    with pytest.raises(B.MoeError) as ei:                  # draft takes at most 8 tokens
+        D.draft(torch.zeros((9, 256), dtype=torch.bfloat16, device="cuda"))
+    assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
+def test_skew_all_tokens_same_experts(ctx):
+    cfg = synth.config_by_name("tiny")
+    c = Case(ctx, cfg, bias="skew")
+    x = synth.make_tokens(cfg, 4, step=51)
+    ref = oracle_verify(c.A, x)
+    assert len(set(map(tuple, ref["ids"].tolist()))) == 1
+    say("skew: verify")
+    r = c.D.verify(x.cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(r["ids"]), ref["ids"])
+    assert rel_err(to_np(r["y"]), ref["y"]) <= TOL_VERIFY
+    refd = oracle_draft(c.A, x)
+    say("skew: draft T=4")
+    rd = c.D.draft(x.cuda())
+    torch.cuda.synchronize()
+    assert rel_err(to_np(rd["y"]), refd["y"]) <= TOL_DRAFT

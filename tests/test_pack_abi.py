@@ -1,0 +1,131 @@
+"""Host-side checks that need no GPU: the packers against the layout formulas documented in
+include/moespeq.h (read back element by element from the byte image), the exported symbols,
+and the host-only entry points."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from paper_2511_14102_amd import binding as B
+from paper_2511_14102_amd import pack
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "moespeq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", hdr))
+    assert {"moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
+            "moe_verify_layer_bf16", "moe_expert_copy_async"} <= names
+    lib = ctypes.CDLL(B.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert names == set(B.EXPORTS)
+
+
+def test_bf16_tile16x32_layout_matches_the_header_formula():
+    rng = np.random.default_rng(0)
+    R, C = 48, 96
+    w = torch.from_numpy(rng.standard_normal((R, C), dtype=np.float32)).to(torch.bfloat16)
+    img = pack.pack_bf16_matrix(w).numpy()
+    assert img.size == R * C * 2
+    bits = w.view(torch.int16).numpy().view(np.uint16)
+    for r in range(R):
+        for c in range(C):
+            tile = (r // 16) * (C // 32) + c // 32
+            lane = ((c % 32) // 8) * 16 + r % 16
+            o = (tile * 64 + lane) * 16 + (c % 8) * 2
+            assert int(img[o]) | (int(img[o + 1]) << 8) == int(bits[r, c])
+
+
+def test_int4_tile64x32_layout_matches_the_header_formula():
+    rng = np.random.default_rng(1)
+    R, C, g = 128, 96, 32
+    q = torch.from_numpy(rng.integers(0, 16, (R, C)).astype(np.uint8))
+    s = torch.from_numpy(rng.random((R, C // g)).astype(np.float16))
+    z = torch.from_numpy(rng.integers(0, 16, (R, C // g)).astype(np.float16))
+    img = pack.pack_int4_codes(q).numpy()
+    assert img.size == R * C // 2
+    words = img.view("<u4")
+    for r in range(R):
+        for c in range(C):
+            tile = (r // 64) * (C // 32) + c // 32
+            d, n = (c % 32) // 8, c % 8
+            p = n // 2 if n % 2 == 0 else 4 + n // 2
+            word = int(words[(tile * 64 + r % 64) * 4 + d])
+            assert (word >> (4 * p)) & 15 == int(q[r, c])
+    simg = pack.pack_int4_sz(s, z).numpy().view("<u2")
+    for r in range(R):
+        for gi in range(C // g):
+            i = ((r // 64) * (C // g) + gi) * 64 + r % 64
+            assert simg[2 * i] == s.numpy().view(np.uint16)[r, gi]
+            assert simg[2 * i + 1] == z.numpy().view(np.uint16)[r, gi]
+
+
+def test_code_pairs_unpack_with_two_masks():
+    # the property the kernel relies on: (word & 0x000F000F) holds codes (0, 1),
+    # (word & 0x00F000F0) >> 4 codes (2, 3), and the same two masks on word >> 8 give (4..7)
+    q = torch.arange(16, dtype=torch.uint8).repeat(64, 2)[:, :32].contiguous()
+    q[:, 8:16] = torch.tensor([3, 14, 1, 7, 9, 0, 15, 6], dtype=torch.uint8)
+    words = pack.pack_int4_codes(q).numpy().view("<u4").reshape(64, 4)
+    for d in range(4):
+        w = int(words[5, d])
+        codes = [int(v) for v in q[5, 8 * d:8 * d + 8]]
+        t = w >> 8
+        got = [w & 0xF, (w >> 16) & 0xF, (w >> 4) & 0xF, (w >> 20) & 0xF,
+               t & 0xF, (t >> 16) & 0xF, (t >> 4) & 0xF, (t >> 20) & 0xF]
+        assert got == codes
+
+
+def test_expert_blob_sizes_and_order():
+    cfg = synth.config_by_name("tiny")
+    d = B.LayerDesc.from_config(cfg)
+    w = synth.make_experts_bf16(cfg, experts=[0])
+    blob = pack.pack_bf16_expert(w["gate"][0], w["up"][0], w["down"][0])
+    assert blob.numel() == B.bf16_expert_bytes(d) == cfg.bf16_expert_bytes
+    n = cfg.hidden * cfg.inter * 2
+    assert torch.equal(blob[n:2 * n], pack.pack_bf16_matrix(w["up"][0]))
+    assert torch.equal(blob[2 * n:], pack.pack_bf16_matrix(w["down"][0]))
+    q, s, z = {}, {}, {}
+    for name in ("gate", "up", "down"):
+        q[name], s[name], z[name] = synth.quantize_rtn_int4(w[name][0], cfg.group_size)
+    qb, sb = pack.pack_int4_expert(q, s, z)
+    assert qb.numel() == B.int4_expert_q_bytes(d) and sb.numel() == B.int4_expert_sz_bytes(d)
+    assert qb.numel() + sb.numel() == cfg.int4_expert_bytes
+
+
+def test_host_only_entry_points():
+    for cfg in synth.CONFIGS:
+        d = B.LayerDesc.from_config(cfg)
+        assert B.validate_desc(d) == 0
+        assert B.workspace_bytes(d, max(cfg.verify_tokens)) > 0
+    bad = [dict(hidden=100), dict(inter=96), dict(n_experts=0), dict(n_experts=257), dict(top_k=0),
+           dict(top_k=17), dict(group_size=48), dict(n_shared=5), dict(hidden=64, group_size=128)]
+    base = synth.config_by_name("tiny")
+    for change in bad:
+        d = B.LayerDesc.from_config(base)
+        for kk, v in change.items():
+            setattr(d, kk, v)
+        assert B.validate_desc(d) == B.MOE_ERR_INVALID_ARG, change
+        assert B.bf16_expert_bytes(d) == 0
+    d = B.LayerDesc.from_config(base)
+    with pytest.raises(B.MoeError):
+        B.workspace_bytes(d, 17)
+    d.top_k = 8
+    with pytest.raises(B.MoeError):
+        B.workspace_bytes(d, 17)
+    assert B.status_string(0) == "ok" and "resident" in B.status_string(-4)
+    lib = B.load_library()
+    # a null context is rejected before any device work
+    assert lib.moe_route_topk(None, ctypes.byref(d), None, None, None, 1, None, None, None, None,
+                              None, None, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_expert_copy_async(None, None, None, 0, None, None) == B.MOE_ERR_INVALID_ARG
+    if not torch.cuda.is_available():
+        with pytest.raises(B.MoeError) as ei:
+            B.Context(0)
+        assert ei.value.status == B.MOE_ERR_HIP
