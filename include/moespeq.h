@@ -249,6 +249,29 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
 int moe_expert_copy_async(moe_ctx *ctx, void *dst_slot_dev, const void *src_pinned_host,
                           size_t bytes, void *copy_stream, void *done_event);
 
+/* ---- measurement aid (not part of the method) ---------------------------------------------- */
+
+#define MOE_KERNEL_ROUTE         0   /* router logits + softmax + top-k (+ fp16 copy of x)   */
+#define MOE_KERNEL_PLAN          1   /* histogram / permutation / expert list / missing list */
+#define MOE_KERNEL_DRAFT_GATEUP  2   /* int4 gate+up GEMV, SwiGLU                            */
+#define MOE_KERNEL_DRAFT_DOWN    3   /* int4 down GEMV                                       */
+#define MOE_KERNEL_BF16_GATEUP   4   /* bf16 gate+up small-M contraction, SwiGLU             */
+#define MOE_KERNEL_BF16_DOWN     5   /* bf16 down small-M contraction                        */
+#define MOE_KERNEL_COMBINE       6   /* weighted sum over a token's experts                  */
+#define MOE_KERNEL_UNION         7   /* expert union                                         */
+#define MOE_KERNEL_COUNT         8
+
+/* With profiling enabled, moe_route_topk / moe_draft_layer_int4 / moe_expert_union /
+ * moe_verify_layer_bf16 bracket each kernel launch with a pair of HIP events recorded on the
+ * call's stream.  Events are created on demand, so this mode allocates and must not be used
+ * under stream capture; it exists for benchmarks only.  Disabling discards pending pairs. */
+int moe_profile_enable(moe_ctx *ctx, int enable);
+/* Waits for every recorded pair of `kernel`, returns the summed elapsed time and the number of
+ * launches since the last read, and clears them.  total_ms / launches are HOST pointers. */
+int moe_profile_read(moe_ctx *ctx, int kernel, double *total_ms, int64_t *launches);
+/* Static name of a MOE_KERNEL_* id (the kernel's function name), "" if out of range. */
+const char *moe_kernel_name(int kernel);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,9 @@ EXPORTS = [
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
     "moe_workspace_bytes", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
+    "moe_profile_enable", "moe_profile_read", "moe_kernel_name",
 ]
+KERNEL_COUNT = 8
 
 
 class MoeError(RuntimeError):
@@ -75,9 +77,13 @@ def load_library():
         L.moe_verify_layer_bf16.argtypes = [vp, dp, vp, vp, vp, vp, sz, vp, vp, i32, i32,
                                             vp, vp, vp, vp, vp, sz, vp]
         L.moe_expert_copy_async.argtypes = [vp, vp, vp, sz, vp, vp]
+        L.moe_profile_enable.argtypes = [vp, i32]
+        L.moe_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double),
+                                       ctypes.POINTER(ctypes.c_int64)]
+        L.moe_kernel_name.argtypes = [i32]; L.moe_kernel_name.restype = ctypes.c_char_p
         for n in EXPORTS:
             if n not in ("moe_status_string", "moe_last_hip_error", "moe_bf16_expert_bytes",
-                         "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes"):
+                         "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes", "moe_kernel_name"):
                 getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -188,3 +194,16 @@ class Context:
             ev = ctypes.c_void_p(done_event.cuda_event)
         self._check(self._lib.moe_expert_copy_async(self._h, _ptr(dst_slot), _ptr(src_pinned), nbytes,
                                                     _stream(copy_stream), ev), "moe_expert_copy_async")
+
+    def profile_enable(self, enable: bool):
+        self._check(self._lib.moe_profile_enable(self._h, int(bool(enable))), "moe_profile_enable")
+
+    def profile_read(self):
+        """{kernel name: (total ms, launches)} since the last read."""
+        out = {}
+        for kid in range(KERNEL_COUNT):
+            ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+            self._check(self._lib.moe_profile_read(self._h, kid, ctypes.byref(ms), ctypes.byref(n)),
+                        "moe_profile_read")
+            out[self._lib.moe_kernel_name(kid).decode()] = (ms.value, n.value)
+        return out

@@ -3,6 +3,8 @@
 // the device (except the documented MOE_VERIFY_STRICT mode).
 #include <string.h>
 #include <new>
+#include <utility>
+#include <vector>
 #include "plan.h"
 
 struct moe_ctx {
@@ -10,6 +12,9 @@ struct moe_ctx {
     int n_cu;
     char arch[64];
     char hip_error[128];
+    bool profiling;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs[MOE_KERNEL_COUNT];   // recorded, not yet read
+    std::vector<hipEvent_t> free_events;
 };
 
 namespace moespeq {
@@ -26,6 +31,7 @@ WsLayout ws_layout(const moe_layer_desc &d, int T)
     L.hh = o;   o += align256(n * d.inter * 2);
     L.hl = o;   o += align256(n * d.inter * 2);
     L.hb = o;   o += align256(rows * d.inter * 2);
+    L.hb_lo = o; o += align256(rows * d.inter * 2);
     L.obuf = o; o += align256(rows * d.hidden * 4);
     L.part = o; o += align256((size_t)kDraftDownSplit * n * d.hidden * 4);
     L.total = o;
@@ -72,6 +78,26 @@ static int hip_status(moe_ctx *ctx, hipError_t e)
     return MOE_ERR_HIP;
 }
 
+// Brackets one kernel launch with an event pair when profiling is on.
+struct ProfScope {
+    moe_ctx *ctx; int kernel; hipStream_t st; hipEvent_t stop;
+    static hipEvent_t take(moe_ctx *c) {
+        hipEvent_t e = nullptr;
+        if (!c->free_events.empty()) { e = c->free_events.back(); c->free_events.pop_back(); }
+        else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+        return e;
+    }
+    ProfScope(moe_ctx *c, int k, hipStream_t s) : ctx(c), kernel(k), st(s), stop(nullptr) {
+        if (!ctx->profiling) return;
+        hipEvent_t start = take(ctx);
+        stop = take(ctx);
+        if (!start || !stop) { stop = nullptr; return; }
+        (void)hipEventRecord(start, st);
+        ctx->pairs[kernel].push_back(std::make_pair(start, stop));
+    }
+    ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
+};
+
 }  // namespace moespeq
 
 using namespace moespeq;
@@ -87,9 +113,10 @@ int moe_create(moe_ctx **out, int device)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return MOE_ERR_HIP;
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return MOE_ERR_HIP;   // kernels are gfx950 only
-    moe_ctx *c = new (std::nothrow) moe_ctx;
+    moe_ctx *c = new (std::nothrow) moe_ctx();
     if (!c) return MOE_ERR_HIP;
-    memset(c, 0, sizeof *c);
+    c->hip_error[0] = 0;
+    c->profiling = false;
     c->device = device;
     c->n_cu = prop.multiProcessorCount;
     strncpy(c->arch, prop.gcnArchName, sizeof(c->arch) - 1);
@@ -99,8 +126,59 @@ int moe_create(moe_ctx **out, int device)
 
 int moe_destroy(moe_ctx *ctx)
 {
+    if (ctx) {
+        (void)moe_profile_enable(ctx, 0);
+        for (hipEvent_t e : ctx->free_events) (void)hipEventDestroy(e);
+    }
     delete ctx;
     return MOE_OK;
+}
+
+int moe_profile_enable(moe_ctx *ctx, int enable)
+{
+    if (!ctx) return MOE_ERR_INVALID_ARG;
+    if (!enable) {
+        for (auto &v : ctx->pairs) {
+            for (auto &p : v) {
+                (void)hipEventSynchronize(p.second);
+                ctx->free_events.push_back(p.first);
+                ctx->free_events.push_back(p.second);
+            }
+            v.clear();
+        }
+    }
+    ctx->profiling = enable != 0;
+    return MOE_OK;
+}
+
+int moe_profile_read(moe_ctx *ctx, int kernel, double *total_ms, int64_t *launches)
+{
+    if (!ctx || kernel < 0 || kernel >= MOE_KERNEL_COUNT || !total_ms || !launches)
+        return MOE_ERR_INVALID_ARG;
+    double sum = 0.0;
+    int64_t n = 0;
+    for (auto &p : ctx->pairs[kernel]) {
+        hipError_t e = hipEventSynchronize(p.second);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.first, p.second);
+        if (e != hipSuccess) return hip_status(ctx, e);
+        sum += ms;
+        ++n;
+        ctx->free_events.push_back(p.first);
+        ctx->free_events.push_back(p.second);
+    }
+    ctx->pairs[kernel].clear();
+    *total_ms = sum;
+    *launches = n;
+    return MOE_OK;
+}
+
+const char *moe_kernel_name(int kernel)
+{
+    static const char *names[MOE_KERNEL_COUNT] = {
+        "route_kernel", "plan_kernel", "draft_gateup_kernel", "draft_down_kernel",
+        "bf16_gateup_kernel", "bf16_down_kernel", "combine_kernel", "union_kernel"};
+    return (kernel >= 0 && kernel < MOE_KERNEL_COUNT) ? names[kernel] : "";
 }
 
 const char *moe_status_string(int status)
@@ -160,8 +238,8 @@ int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
     if (!aligned(counts, 4) || !aligned(offsets, 4) || !aligned(perm, 4)) return MOE_ERR_INVALID_ARG;
     const Shape s = make_shape(desc, T);
     hipStream_t st = (hipStream_t)stream;
-    launch_route(s, x, wr, bias, ids, w, conf, nullptr, nullptr, st);
-    if (nperm) launch_perm(s, ids, counts, offsets, perm, st);
+    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st); launch_route(s, x, wr, bias, ids, w, conf, nullptr, nullptr, st); }
+    if (nperm) { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_perm(s, ids, counts, offsets, perm, st); }
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -190,7 +268,8 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
-    launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, ws + L.xh, plan->x_unscale, st);
+    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
+      launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, ws + L.xh, plan->x_unscale, st); }
     PlanArgs a;
     memset(&a, 0, sizeof a);
     a.plan = plan; a.mode = 0;
@@ -198,15 +277,20 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     a.w1 = routed->sz; a.stride1 = routed->expert_stride_sz;
     a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
     a.ids_out = ids_out; a.conf_out = conf_out;
-    launch_plan(s, a, st);
-    launch_draft_gateup(s, plan, ws + L.xh, ws + L.hh, ws + L.hl, st);
-    launch_draft_down(s, plan, ws + L.hh, ws + L.hl, (float *)(ws + L.part), st);
+    { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_plan(s, a, st); }
+    { ProfScope p(ctx, MOE_KERNEL_DRAFT_GATEUP, st);
+      launch_draft_gateup(s, plan, ws + L.xh, ws + L.hh, ws + L.hl, st); }
+    { ProfScope p(ctx, MOE_KERNEL_DRAFT_DOWN, st);
+      launch_draft_down(s, plan, ws + L.hh, ws + L.hl, (float *)(ws + L.part), st); }
     if (s.S > 0) {   // shared experts stay 16-bit in the draft model (section 3.4.2)
-        launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, st);
-        launch_bf16_down(s, plan, 0, s.S, ws + L.hb, (float *)(ws + L.obuf), st);
+        { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st); 
+          launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, ws + L.hb_lo, st); }
+        { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);
+          launch_bf16_down(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, (float *)(ws + L.obuf), st); }
     }
-    launch_combine(s, plan, (const float *)(ws + L.part), kDraftDownSplit,
-                   (const float *)(ws + L.obuf), 0, 0, y, st);
+    { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
+      launch_combine(s, plan, (const float *)(ws + L.part), kDraftDownSplit,
+                     (const float *)(ws + L.obuf), 0, 0, y, st); }
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -220,8 +304,9 @@ int moe_expert_union(moe_ctx *ctx, const int32_t *ids, int n_ids, int n_experts,
     if (!aligned(ids, 4) || !aligned(slot_of_expert, 4) || !aligned(mask, 8) || !aligned(list, 4) ||
         !aligned(n_list, 4) || !aligned(missing, 4) || !aligned(n_missing, 4))
         return MOE_ERR_INVALID_ARG;
-    launch_union(ids, n_ids, n_experts, slot_of_expert, mask, list, n_list, missing, n_missing,
-                 (hipStream_t)stream);
+    { ProfScope p(ctx, MOE_KERNEL_UNION, (hipStream_t)stream);
+      launch_union(ids, n_ids, n_experts, slot_of_expert, mask, list, n_list, missing, n_missing,
+                   (hipStream_t)stream); }
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -251,7 +336,8 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
-    launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, nullptr, nullptr, st);
+    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
+      launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, nullptr, nullptr, st); }
     PlanArgs a;
     memset(&a, 0, sizeof a);
     a.plan = plan; a.mode = 1;
@@ -261,12 +347,14 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     a.flags = flags;
     a.ids_out = ids_out;
     a.missing = missing; a.n_missing = n_missing;
-    launch_plan(s, a, st);
+    { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_plan(s, a, st); }
     const int nexp = s.S + (s.E < s.T * s.k ? s.E : s.T * s.k);
-    launch_bf16_gateup(s, plan, 0, nexp, x, ws + L.hb, st);
-    launch_bf16_down(s, plan, 0, nexp, ws + L.hb, (float *)(ws + L.obuf), st);
-    launch_combine(s, plan, (const float *)(ws + L.obuf), 1, (const float *)(ws + L.obuf),
-                   (flags & MOE_VERIFY_ACCUMULATE) ? 1 : 0, 1, y, st);
+    { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st); launch_bf16_gateup(s, plan, 0, nexp, x, ws + L.hb, nullptr, st); }
+    { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);
+      launch_bf16_down(s, plan, 0, nexp, ws + L.hb, nullptr, (float *)(ws + L.obuf), st); }
+    { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
+      launch_combine(s, plan, (const float *)(ws + L.obuf), 1, (const float *)(ws + L.obuf),
+                     (flags & MOE_VERIFY_ACCUMULATE) ? 1 : 0, 1, y, st); }
     int rc = hip_status(ctx, hipGetLastError());
     if (rc != MOE_OK) return rc;
     if (flags & MOE_VERIFY_STRICT) {

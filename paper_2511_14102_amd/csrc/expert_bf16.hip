@@ -34,9 +34,12 @@ __device__ inline f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
 
 // h[row, i] = silu(Wg x)[i] * (Wu x)[i] for the rows (tokens) of one expert and 16 values of i.
 // grid.x = I / 16, grid.y = experts; block = 4 waves splitting K = H.
+// kHiLo: also write h - bf16(h) (rounded to bf16) to hb_lo, for callers that need h to ~16 bits.
+template <bool kHiLo>
 __global__ __launch_bounds__(kWaves * 64)
 void bf16_gateup_kernel(const Plan *__restrict__ plan, int first_active,
-                        const uint16_t *__restrict__ x, uint16_t *__restrict__ hb, int H, int I)
+                        const uint16_t *__restrict__ x, uint16_t *__restrict__ hb,
+                        uint16_t *__restrict__ hb_lo, int H, int I)
 {
     const int u = first_active + blockIdx.y;
     if (u >= plan->n_active) return;
@@ -86,7 +89,7 @@ void bf16_gateup_kernel(const Plan *__restrict__ plan, int first_active,
     }
     __syncthreads();
     if (wave != 0 || n >= cnt) return;
-    uint16_t out[4];
+    uint16_t out[4], out_lo[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float g = 0.f, v = 0.f;
@@ -94,18 +97,25 @@ void bf16_gateup_kernel(const Plan *__restrict__ plan, int first_active,
         for (int w = 0; w < kWaves; ++w) { g += s_red[w][0][i][lane]; v += s_red[w][1][i][lane]; }
         float h = g / (1.f + expf(-g)) * v;
         out[i] = f32_to_bf16_rne(h);
+        if (kHiLo) out_lo[i] = f32_to_bf16_rne(h - __uint_as_float((uint32_t)out[i] << 16));
     }
     // D layout: lane holds rows c*4 .. c*4+3 of column n
-    uint2 pk = make_uint2((uint32_t)out[0] | ((uint32_t)out[1] << 16),
-                          (uint32_t)out[2] | ((uint32_t)out[3] << 16));
-    *reinterpret_cast<uint2 *>(hb + (size_t)(off + n) * I + blockIdx.x * 16 + c * 4) = pk;
+    const size_t o = (size_t)(off + n) * I + blockIdx.x * 16 + c * 4;
+    *reinterpret_cast<uint2 *>(hb + o) = make_uint2((uint32_t)out[0] | ((uint32_t)out[1] << 16),
+                                                    (uint32_t)out[2] | ((uint32_t)out[3] << 16));
+    if (kHiLo)
+        *reinterpret_cast<uint2 *>(hb_lo + o) = make_uint2((uint32_t)out_lo[0] | ((uint32_t)out_lo[1] << 16),
+                                                           (uint32_t)out_lo[2] | ((uint32_t)out_lo[3] << 16));
 }
 
 // obuf[row, r] = row_w[row] * (Wd h[row])[r] for 16 values of r.
 // grid.x = H / 16, grid.y = experts; block = 4 waves splitting K = I.
+// kHiLo: the operand is hb + hb_lo (two MFMAs per tile).
+template <bool kHiLo>
 __global__ __launch_bounds__(kWaves * 64)
 void bf16_down_kernel(const Plan *__restrict__ plan, int first_active,
-                      const uint16_t *__restrict__ hb, float *__restrict__ obuf, int H, int I)
+                      const uint16_t *__restrict__ hb, const uint16_t *__restrict__ hb_lo,
+                      float *__restrict__ obuf, int H, int I)
 {
     const int u = first_active + blockIdx.y;
     if (u >= plan->n_active) return;
@@ -119,25 +129,36 @@ void bf16_down_kernel(const Plan *__restrict__ plan, int first_active,
     const size_t mat = (size_t)(I / 16) * (H / 32) * 64;
     const u32x4 *wd = reinterpret_cast<const u32x4 *>(plan->act_w0[u]) + 2 * mat + (size_t)blockIdx.x * U * 64 + lane;
     const bool live = n < cnt;
-    const uint16_t *hrow = hb + (size_t)(off + (live ? n : 0)) * I + c * 8;
+    const size_t hoff = (size_t)(off + (live ? n : 0)) * I + c * 8;
+    const uint16_t *hrow = hb + hoff;
+    const uint16_t *lrow = kHiLo ? hb_lo + hoff : nullptr;
     const int ku0 = (wave * U) / kWaves, ku1 = ((wave + 1) * U) / kWaves;
+    const u32x4 zero = {0u, 0u, 0u, 0u};
 
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     int ku = ku0;
     for (; ku + kUnroll <= ku1; ku += kUnroll) {
-        u32x4 a[kUnroll], hv[kUnroll];
+        u32x4 a[kUnroll], hv[kUnroll], lv[kUnroll];
 #pragma unroll
         for (int i = 0; i < kUnroll; ++i) {
             a[i] = __builtin_nontemporal_load(wd + (size_t)(ku + i) * 64);
-            hv[i] = live ? *reinterpret_cast<const u32x4 *>(hrow + (ku + i) * 32) : (u32x4){0u, 0u, 0u, 0u};
+            hv[i] = live ? *reinterpret_cast<const u32x4 *>(hrow + (ku + i) * 32) : zero;
+            if (kHiLo) lv[i] = live ? *reinterpret_cast<const u32x4 *>(lrow + (ku + i) * 32) : zero;
         }
 #pragma unroll
-        for (int i = 0; i < kUnroll; ++i) acc = mfma16(a[i], hv[i], acc);
+        for (int i = 0; i < kUnroll; ++i) {
+            acc = mfma16(a[i], hv[i], acc);
+            if (kHiLo) acc = mfma16(a[i], lv[i], acc);
+        }
     }
     for (; ku < ku1; ++ku) {
         u32x4 a = __builtin_nontemporal_load(wd + (size_t)ku * 64);
-        u32x4 hv = live ? *reinterpret_cast<const u32x4 *>(hrow + ku * 32) : (u32x4){0u, 0u, 0u, 0u};
+        u32x4 hv = live ? *reinterpret_cast<const u32x4 *>(hrow + ku * 32) : zero;
         acc = mfma16(a, hv, acc);
+        if (kHiLo) {
+            u32x4 lv = live ? *reinterpret_cast<const u32x4 *>(lrow + ku * 32) : zero;
+            acc = mfma16(a, lv, acc);
+        }
     }
 
     __shared__ float s_red[kWaves][4][64];
@@ -215,19 +236,29 @@ void combine_kernel(const Plan *__restrict__ plan, const float *__restrict__ rou
 }  // namespace
 
 void launch_bf16_gateup(const Shape &s, const Plan *plan, int first_active, int n_active_max,
-                        const void *x, void *hb, hipStream_t st)
+                        const void *x, void *hb, void *hb_lo, hipStream_t st)
 {
     if (n_active_max <= 0) return;
-    hipLaunchKernelGGL(bf16_gateup_kernel, dim3(s.I / 16, n_active_max), dim3(kWaves * 64), 0, st,
-                       plan, first_active, (const uint16_t *)x, (uint16_t *)hb, s.H, s.I);
+    const dim3 grid(s.I / 16, n_active_max), block(kWaves * 64);
+    if (hb_lo)
+        hipLaunchKernelGGL(bf16_gateup_kernel<true>, grid, block, 0, st, plan, first_active,
+                           (const uint16_t *)x, (uint16_t *)hb, (uint16_t *)hb_lo, s.H, s.I);
+    else
+        hipLaunchKernelGGL(bf16_gateup_kernel<false>, grid, block, 0, st, plan, first_active,
+                           (const uint16_t *)x, (uint16_t *)hb, (uint16_t *)nullptr, s.H, s.I);
 }
 
 void launch_bf16_down(const Shape &s, const Plan *plan, int first_active, int n_active_max,
-                      const void *hb, float *obuf, hipStream_t st)
+                      const void *hb, const void *hb_lo, float *obuf, hipStream_t st)
 {
     if (n_active_max <= 0) return;
-    hipLaunchKernelGGL(bf16_down_kernel, dim3(s.H / 16, n_active_max), dim3(kWaves * 64), 0, st,
-                       plan, first_active, (const uint16_t *)hb, obuf, s.H, s.I);
+    const dim3 grid(s.H / 16, n_active_max), block(kWaves * 64);
+    if (hb_lo)
+        hipLaunchKernelGGL(bf16_down_kernel<true>, grid, block, 0, st, plan, first_active,
+                           (const uint16_t *)hb, (const uint16_t *)hb_lo, obuf, s.H, s.I);
+    else
+        hipLaunchKernelGGL(bf16_down_kernel<false>, grid, block, 0, st, plan, first_active,
+                           (const uint16_t *)hb, (const uint16_t *)nullptr, obuf, s.H, s.I);
 }
 
 void launch_combine(const Shape &s, const Plan *plan, const float *routed, int nsplit,

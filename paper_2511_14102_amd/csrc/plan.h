@@ -41,7 +41,8 @@ struct Shape {
 
 // Workspace carve-up (byte offsets from a 256-byte aligned base).
 struct WsLayout {
-    size_t plan, xh, hh, hl, hb, obuf, part, total;   // xh: fp16 x; hh/hl: fp16 hi/lo of h; hb: bf16 h
+    // xh: fp16 x; hh/hl: fp16 hi/lo of h (int4 path); hb/hb_lo: bf16 h and its bf16 remainder
+    size_t plan, xh, hh, hl, hb, hb_lo, obuf, part, total;
 };
 WsLayout ws_layout(const moe_layer_desc &d, int max_tokens);
 
@@ -77,10 +78,11 @@ void launch_draft_down(const Shape &s, const Plan *plan, const void *hh, const v
                        float *part, hipStream_t st);
 
 // expert_bf16.hip
+// hb_lo != nullptr: the intermediate is kept as a bf16 hi + lo pair (draft-pass precision)
 void launch_bf16_gateup(const Shape &s, const Plan *plan, int first_active, int n_active_max,
-                        const void *x, void *hb, hipStream_t st);
+                        const void *x, void *hb, void *hb_lo, hipStream_t st);
 void launch_bf16_down(const Shape &s, const Plan *plan, int first_active, int n_active_max,
-                      const void *hb, float *obuf, hipStream_t st);
+                      const void *hb, const void *hb_lo, float *obuf, hipStream_t st);
 // y[t] = (accumulate ? y[t] : 0) + sum over the token's live routed rows of
 // sum_{split < nsplit} routed[split][row] + sum over its live shared rows of obuf[row];
 // routed is [nsplit][T*k][H] fp32, obuf is [rows][H] fp32 indexed by row number.

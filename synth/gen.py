@@ -136,27 +136,38 @@ def make_tokens(cfg: LayerConfig, T: int, layer: int = 0, step: int = 0,
 
 
 def make_layer(cfg: LayerConfig, layer: int = 0, bias: Optional[str] = None,
-               quantize: bool = True) -> Dict[str, object]:
-    """One full layer on the CPU in the logical layouts listed in the module docstring.
+               quantize: bool = True, device: str = "cpu",
+               quant_device: Optional[str] = None) -> Dict[str, object]:
+    """One full layer in the logical layouts listed in the module docstring.
 
     bias: None -> what cfg.router asks for ('zipf' -> zipf_bias, otherwise no bias);
           'skew' -> skew_bias; 'none' -> no bias.
+    device: "cpu" draws every tensor from the numpy streams (what the oracle sees);
+            a GPU device draws the expert weights there with torch's generator seeded with
+            layer_seed (benchmark filler layers; router and bias are still the CPU ones).
+    quant_device: where the RTN quantiser runs (same fp64 elementwise arithmetic, so the same
+            result); results are returned on `device`.
     """
-    E, S = cfg.n_experts, cfg.n_shared
+    E = cfg.n_experts
     L: Dict[str, object] = {"cfg": cfg, "layer": layer}
     L["router"] = make_router(cfg, layer)
     mode = bias or ("zipf" if cfg.router == "zipf" else "none")
     L["router_bias"] = {"zipf": lambda: zipf_bias(cfg, layer),
                         "skew": lambda: skew_bias(cfg),
                         "none": lambda: None}[mode]()
-    w = make_experts_bf16(cfg, layer)
+    tgen = None
+    if device != "cpu":
+        tgen = torch.Generator(device=device)
+        tgen.manual_seed(layer_seed(cfg, layer))
+    w = make_experts_bf16(cfg, layer, device=device, tgen=tgen)
     L.update(w)
     if quantize:
+        qdev = quant_device or device
         for name in ("gate", "up", "down"):
             qs, ss, zs = [], [], []
             for e in range(E):          # one expert at a time bounds the fp64 temporaries
-                q, s, z = quantize_rtn_int4(w[name][e], cfg.group_size)
-                qs.append(q); ss.append(s); zs.append(z)
+                q, s, z = quantize_rtn_int4(w[name][e].to(qdev), cfg.group_size)
+                qs.append(q.to(device)); ss.append(s.to(device)); zs.append(z.to(device))
             L["q_" + name] = torch.stack(qs)
             L["s_" + name] = torch.stack(ss)
             L["z_" + name] = torch.stack(zs)

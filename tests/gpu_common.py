@@ -20,19 +20,9 @@ def say(*a):
 
 
 def build_layer(cfg, layer=0, bias=None, quantize=True):
-    """synth.make_layer, but with the RTN quantiser run on the GPU if available."""
-    L = synth.make_layer(cfg, layer, bias=bias, quantize=False)
-    if quantize:
-        dev = "cuda:0" if torch.cuda.is_available() else "cpu"
-        for name in ("gate", "up", "down"):
-            qs, ss, zs = [], [], []
-            for e in range(cfg.n_experts):
-                q, s, z = synth.quantize_rtn_int4(L[name][e].to(dev), cfg.group_size)
-                qs.append(q.cpu()); ss.append(s.cpu()); zs.append(z.cpu())
-            L["q_" + name] = torch.stack(qs)
-            L["s_" + name] = torch.stack(ss)
-            L["z_" + name] = torch.stack(zs)
-    return L
+    """synth.make_layer on the CPU streams, with the RTN quantiser run on the GPU if available."""
+    qdev = "cuda:0" if torch.cuda.is_available() else None
+    return synth.make_layer(cfg, layer, bias=bias, quantize=quantize, quant_device=qdev)
 
 
 def tokens_with_clear_routing(cfg, A, T, layer=0, step=0, kind=None):
