@@ -167,12 +167,9 @@ def main():
                         "us_per_launch": round(kk["us_avg"], 2)}
     extra = {}
     if kern:
-        dg, dd = kern.get("draft_gateup_kernel"), kern.get("draft_down_kernel")
-        if dg and dd:
-            gu_b = k * (2 * H * I // 2 + 2 * H * I // g * 4)
-            dn_b = k * (H * I // 2 + H * I // g * 4)
-            extra["draft_gateup_GBs"] = round(gu_b / (dg["us_avg"] * 1e-6) / 1e9, 1)
-            extra["draft_down_GBs"] = round(dn_b / (dd["us_avg"] * 1e-6) / 1e9, 1)
+        df = kern.get("draft_fused_kernel")
+        if df:
+            extra["draft_fused_GBs"] = round((k * int4_expert + E * H * 2 + H * 6) / (df["us_avg"] * 1e-6) / 1e9, 1)
         bd = kern.get("bf16_down_kernel")
         if bd and S == 0:
             extra["bf16_down_GBs"] = round(mean_u_run * H * I * 2 / (bd["us_avg"] * 1e-6) / 1e9, 1)

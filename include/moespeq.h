@@ -39,16 +39,23 @@
  *  bf16 expert blob = [gate I x H | up I x H | down H x I], each tile16x32, contiguous,
  *      moe_bf16_expert_bytes() bytes.  One blob fills one slot of the expert cache.
  *
- *  int4 matrix, codes q[R][C] in 0..15, fp16 scale s and zero z per (row, group of g
- *  consecutive inputs), W = (q - z) * s  (R % 64 == 0, C % 32 == 0), "tile64x32":
- *      codes: 1 KiB tiles, tile = (r / 64) * (C / 32) + c / 32; inside a tile lane = r % 64
- *      owns 16 bytes = 4 little-endian 32-bit words; word d holds the 8 codes
- *      c % 32 in [8d, 8d + 8); code number n of the word (n = c % 8) sits in bits
- *      [4 * p, 4 * p + 4) with p = n / 2 for even n and p = 4 + n / 2 for odd n.
- *      scale/zero: for tile row-block r / 64 and group c / g, 64 lanes x (fp16 s, fp16 z):
- *      index ((r / 64) * (C / g) + c / g) * 64 + r % 64, 4 bytes each (s in the low half).
- *  int4 expert = codes blob [gate | up | down] of moe_int4_expert_q_bytes() bytes and
- *      scale/zero blob [gate | up | down] of moe_int4_expert_sz_bytes() bytes.
+ *  int4 expert: codes q in 0..15, fp16 scale s and zero z per (row, group of g consecutive
+ *  inputs), W = (q - z) * s.  32 codes of one row are a 16-byte unit = 4 little-endian 32-bit
+ *  words; word d holds codes [8d, 8d + 8) of the unit; code number n of the word sits in bits
+ *  [4p, 4p + 4) with p = n / 2 for even n and p = 4 + n / 2 for odd n (so `word & 0x000F000F`
+ *  is the pair of codes 0, 1 and so on).  Units are grouped in 1 KiB tiles of 64 lanes:
+ *    gate/up part ("slices" of 32 intermediate rows, I / 32 of them): tile (slice, u) for input
+ *      unit u = c / 32 at index slice * (H / 32) + u; lane l < 32 is gate row 32 slice + l,
+ *      lane l >= 32 is up row 32 slice + l - 32.
+ *    down part, after the (I / 32) * (H / 32) gate/up tiles: tile (slice, rt) at index
+ *      slice * (H / 64) + rt holds, in lane l, output row 64 rt + l, input columns
+ *      [32 slice, 32 slice + 32).
+ *    codes blob = moe_int4_expert_q_bytes() = 3 H I / 2 bytes.
+ *  scale/zero blob: 4-byte entries (fp16 s in the low half, fp16 z in the high half):
+ *    gate/up part: entry ((slice * (H / g) + group) * 64 + lane), lanes as above, group = c / g;
+ *    down part, after the (I / 32) * (H / g) * 64 gate/up entries: entry (group * H + row),
+ *      group = input column / g, row = output row.
+ *    moe_int4_expert_sz_bytes() = 3 H I / g * 4 bytes.
  */
 #ifndef MOESPEQ_H
 #define MOESPEQ_H
@@ -121,9 +128,14 @@ size_t moe_int4_expert_q_bytes(const moe_layer_desc *desc);
 size_t moe_int4_expert_sz_bytes(const moe_layer_desc *desc);
 
 /* Bytes of device workspace that moe_draft_layer_int4 / moe_verify_layer_bf16 need for up to
- * `max_tokens` tokens per call (256-byte aligned base).  Contents need no initialisation and
- * carry nothing from call to call. */
+ * `max_tokens` tokens per call (256-byte aligned base). */
 int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *bytes);
+
+/* Puts a workspace into its idle state (enqueues a fill kernel on `stream`; workspace_bytes a
+ * multiple of 4).  Required once after allocation, before the first draft call: the draft
+ * kernel keeps cross-workgroup counters and an fp32 accumulator there, which it expects zero
+ * on entry and leaves zero on exit.  Nothing else is carried from call to call. */
+int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- router: softmax + top-k, histogram, permutation --------------------------------- */
 
@@ -164,7 +176,7 @@ int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
  *   route as in moe_route_topk, then
  *   y[t] = sum_j w[t,j] FFN_{ids[t,j]}(x[t]) + sum_s FFN_shared_s(x[t])
  *   FFN(x) = Wd ( silu(Wg x) (.) (Wu x) ),  routed experts with W = (q - z) * s,
- *   products accumulated in fp32, the intermediate kept in more than fp16 precision,
+ *   products accumulated in fp32, the intermediate carried with 16 significant bits,
  *   y written as fp32.
  *
  * routed: the E int4 experts (struct above).  shared_bf16: S contiguous bf16 expert blobs, or
@@ -173,7 +185,9 @@ int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
  * y_f32 [T,H]; ids_out [T,k] int32 in rank order; conf_out [T,k] fp32 or NULL.  ids_out /
  * conf_out may point into a larger [step, layer, T, k] buffer so that a whole window can be
  * copied to the host at once (section 4.1.2, batched device-to-host transfer).
- * Activations must satisfy |x| < 2^100 and the SwiGLU intermediate |h| < 65504.
+ * `workspace` must be in its idle state (moe_workspace_init once; every draft call restores
+ * it).  y is summed with fp32 atomics, so its last bits may differ from run to run; ids and
+ * confidences do not.
  */
 int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
                          const void *x_bf16, const void *w_router_bf16,
@@ -253,8 +267,8 @@ int moe_expert_copy_async(moe_ctx *ctx, void *dst_slot_dev, const void *src_pinn
 
 #define MOE_KERNEL_ROUTE         0   /* router logits + softmax + top-k (+ fp16 copy of x)   */
 #define MOE_KERNEL_PLAN          1   /* histogram / permutation / expert list / missing list */
-#define MOE_KERNEL_DRAFT_GATEUP  2   /* int4 gate+up GEMV, SwiGLU                            */
-#define MOE_KERNEL_DRAFT_DOWN    3   /* int4 down GEMV                                       */
+#define MOE_KERNEL_DRAFT_FUSED   2   /* router + top-k + int4 SwiGLU experts, one launch     */
+#define MOE_KERNEL_RESERVED      3
 #define MOE_KERNEL_BF16_GATEUP   4   /* bf16 gate+up small-M contraction, SwiGLU             */
 #define MOE_KERNEL_BF16_DOWN     5   /* bf16 down small-M contraction                        */
 #define MOE_KERNEL_COMBINE       6   /* weighted sum over a token's experts                  */

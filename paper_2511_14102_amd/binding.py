@@ -19,7 +19,7 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_MISSING_EXP
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_status_string", "moe_last_hip_error", "moe_validate_desc",
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
-    "moe_workspace_bytes", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
+    "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
     "moe_profile_enable", "moe_profile_read", "moe_kernel_name",
 ]
@@ -70,6 +70,7 @@ def load_library():
         for n in ("moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes"):
             getattr(L, n).argtypes = [dp]; getattr(L, n).restype = sz
         L.moe_workspace_bytes.argtypes = [dp, i32, ctypes.POINTER(sz)]
+        L.moe_workspace_init.argtypes = [vp, vp, sz, vp]
         L.moe_route_topk.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_draft_layer_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                            vp, vp, vp, vp, sz, vp]
@@ -156,6 +157,11 @@ class Context:
             if rc == MOE_ERR_HIP:
                 extra = " [" + self._lib.moe_last_hip_error(self._h).decode() + "]"
             raise MoeError(rc, what + extra)
+
+    def workspace_init(self, workspace, stream=None):
+        self._check(self._lib.moe_workspace_init(self._h, _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(),
+                                                 _stream(stream)), "moe_workspace_init")
 
     def route_topk(self, desc, x, w_router, router_bias, T, topk_ids, topk_w, topk_conf=None,
                    counts=None, offsets=None, perm=None, stream=None):

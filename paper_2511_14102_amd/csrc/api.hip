@@ -26,14 +26,14 @@ WsLayout ws_layout(const moe_layer_desc &d, int T)
     WsLayout L;
     const size_t n = (size_t)T * d.top_k, rows = n + (size_t)T * d.n_shared;
     size_t o = 0;
-    L.plan = o; o += align256(sizeof(Plan));
-    L.xh = o;   o += align256((size_t)T * d.hidden * 2);
-    L.hh = o;   o += align256(n * d.inter * 2);
-    L.hl = o;   o += align256(n * d.inter * 2);
-    L.hb = o;   o += align256(rows * d.inter * 2);
-    L.hb_lo = o; o += align256(rows * d.inter * 2);
-    L.obuf = o; o += align256(rows * d.hidden * 4);
-    L.part = o; o += align256((size_t)kDraftDownSplit * n * d.hidden * 4);
+    L.sync = o;   o += align256(sizeof(DraftSync));
+    // fixed sizes: the idle-state regions must sit at the same place whatever T a call uses
+    L.yacc = o;   o += align256((size_t)MOE_MAX_DRAFT_TOKENS * d.hidden * 4);
+    L.logits = o; o += align256((size_t)MOE_MAX_TOKENS * d.n_experts * 8);
+    L.plan = o;   o += align256(sizeof(Plan));
+    L.hb = o;     o += align256(rows * d.inter * 2);
+    L.hb_lo = o;  o += align256(rows * d.inter * 2);
+    L.obuf = o;   o += align256(rows * d.hidden * 4);
     L.total = o;
     return L;
 }
@@ -176,7 +176,7 @@ int moe_profile_read(moe_ctx *ctx, int kernel, double *total_ms, int64_t *launch
 const char *moe_kernel_name(int kernel)
 {
     static const char *names[MOE_KERNEL_COUNT] = {
-        "route_kernel", "plan_kernel", "draft_gateup_kernel", "draft_down_kernel",
+        "route_kernel", "plan_kernel", "draft_fused_kernel", "(unused)",
         "bf16_gateup_kernel", "bf16_down_kernel", "combine_kernel", "union_kernel"};
     return (kernel >= 0 && kernel < MOE_KERNEL_COUNT) ? names[kernel] : "";
 }
@@ -223,6 +223,14 @@ int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *byte
     return MOE_OK;
 }
 
+int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < 256 || workspace_bytes % 4)
+        return MOE_ERR_INVALID_ARG;
+    launch_zero(workspace, workspace_bytes, (hipStream_t)stream);
+    return hip_status(ctx, hipGetLastError());
+}
+
 int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
                    const void *x, const void *wr, const float *bias, int T,
                    int32_t *ids, float *w, float *conf,
@@ -238,7 +246,7 @@ int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
     if (!aligned(counts, 4) || !aligned(offsets, 4) || !aligned(perm, 4)) return MOE_ERR_INVALID_ARG;
     const Shape s = make_shape(desc, T);
     hipStream_t st = (hipStream_t)stream;
-    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st); launch_route(s, x, wr, bias, ids, w, conf, nullptr, nullptr, st); }
+    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st); launch_route(s, x, wr, bias, ids, w, conf, st); }
     if (nperm) { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_perm(s, ids, counts, offsets, perm, st); }
     return hip_status(ctx, hipGetLastError());
 }
@@ -268,29 +276,23 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
-    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
-      launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, ws + L.xh, plan->x_unscale, st); }
-    PlanArgs a;
-    memset(&a, 0, sizeof a);
-    a.plan = plan; a.mode = 0;
-    a.w0 = routed->q; a.stride0 = routed->expert_stride_q;
-    a.w1 = routed->sz; a.stride1 = routed->expert_stride_sz;
-    a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
-    a.ids_out = ids_out; a.conf_out = conf_out;
-    { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_plan(s, a, st); }
-    { ProfScope p(ctx, MOE_KERNEL_DRAFT_GATEUP, st);
-      launch_draft_gateup(s, plan, ws + L.xh, ws + L.hh, ws + L.hl, st); }
-    { ProfScope p(ctx, MOE_KERNEL_DRAFT_DOWN, st);
-      launch_draft_down(s, plan, ws + L.hh, ws + L.hl, (float *)(ws + L.part), st); }
+    DraftFusedArgs a;
+    a.x = x; a.wr = wr; a.bias = bias;
+    a.q = routed->q; a.sz = routed->sz;
+    a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
+    a.sync = (DraftSync *)(ws + L.sync); a.logits = (double *)(ws + L.logits);
+    a.yacc = (float *)(ws + L.yacc);
+    a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
+    a.plan = plan; a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
+    { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_fused(s, a, st); }
     if (s.S > 0) {   // shared experts stay 16-bit in the draft model (section 3.4.2)
-        { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st); 
+        { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st);
           launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, ws + L.hb_lo, st); }
         { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);
           launch_bf16_down(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, (float *)(ws + L.obuf), st); }
+        { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
+          launch_combine(s, plan, nullptr, 0, (const float *)(ws + L.obuf), 1, 0, y, st); }
     }
-    { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
-      launch_combine(s, plan, (const float *)(ws + L.part), kDraftDownSplit,
-                     (const float *)(ws + L.obuf), 0, 0, y, st); }
     return hip_status(ctx, hipGetLastError());
 }
 
@@ -337,7 +339,7 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
     { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
-      launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, nullptr, nullptr, st); }
+      launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, st); }
     PlanArgs a;
     memset(&a, 0, sizeof a);
     a.plan = plan; a.mode = 1;

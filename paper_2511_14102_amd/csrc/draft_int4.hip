@@ -1,58 +1,71 @@
-// Draft-pass expert kernels: SwiGLU FFN on group-wise int4 weights with the dequantisation
-// fused into the matrix-vector products (gfx950).
+// Draft-pass kernel: router, top-k and the SwiGLU FFN of the selected experts on group-wise
+// int4 weights, dequantisation fused into the matrix-vector products, ONE launch per call
+// (gfx950).
 //
-// Paper section 3.4.3: the draft pass must run the quantised experts without the launch and
-// utilisation losses of per-expert small GEMMs; section 4.1.3: 4-bit weights in groups along
-// the input dimension.  W = (q - z) * s, so for one output row and one group G
-//     sum_{c in G} W[c] v[c] = s * ( sum_c q[c] v[c]  -  z * sum_c v[c] ),
-// i.e. the inner loop needs only the integer codes: the codes are turned into exact fp16
-// integers with two bit operations and one packed fp16 op per pair and fed to the
-// fp16-pair dot product with fp32 accumulation; scale and zero are applied once per group.
+// Paper section 3.4.3: the draft pass has to avoid the launch and utilisation losses of
+// per-expert small GEMMs (one monolithic expert-fused kernel); section 4.1.3: 4-bit weights in
+// groups along the input dimension; section 3.3.1: (expert id, confidence) per token and layer
+// is recorded for the lookahead buffer.
 //
-// Mapping: one lane owns one output row ("tile64x32" layout: a wave's 16-byte loads of one
-// tile are 1 KiB contiguous), so no cross-lane reduction is needed; the activation values of a
-// step are wave-uniform and come through scalar loads.  K is split over the waves of a
-// workgroup (and, for the down projection, over several workgroups) and recombined in a fixed
-// order.
+// Arithmetic.  W = (q - z) * s, so for one output row and one group G of inputs
+//     sum_{c in G} W[c] v[c] = s * ( sum_c (128 + q[c]) v[c]  -  (z + 128) * sum_c v[c] ).
+// 0x4300 is bf16 128.0 with a zero mantissa, so or-ing a code into mantissa bits 0-3 gives the
+// bf16 value 128 + q exactly: the inner loop is shift / and-or / bf16-pair dot product with fp32
+// accumulation; scale, zero and the 128 offset are applied once per group.  Activations stay
+// bf16 (exact); the SwiGLU intermediate is carried as a bf16 hi + lo pair (16 significant bits).
+//
+// Work decomposition ("slice fusion").  A work item is (expert, slice of 32 intermediate
+// rows): its workgroup computes the 32 gate and 32 up pre-activations (one lane per row, K = H
+// split over the 8 waves), h = silu(gate) * up, and immediately multiplies h into the 32
+// matching columns of the down projection for all H outputs (one lane per output row),
+// adding the partial outputs into an fp32 accumulator with atomics.  Nothing but the router
+// result crosses workgroups before the end, so every weight byte can be requested as soon as
+// the expert ids are known.  The last workgroup to finish copies the accumulator to y and
+// clears it, so the workspace returns to its idle (all-zero) state.
+//
+// Cross-workgroup protocol (bounded waits only):
+//   1. row e of the router is reduced by workgroup e (mod grid); it publishes logits[t][e] and
+//      increments route_count (release);
+//   2. every workgroup waits until route_count == E (acquire, bounded spin), then selects the
+//      top-k itself (identical in all workgroups);
+//   3. after its atomics every workgroup increments done_count (release); the one that draws the
+//      last ticket finalises.
 #include "plan.h"
 
 namespace moespeq {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kGuWaves = 8;       // waves per workgroup (K-split) in the gate/up kernel
-constexpr int kDownWaves = 4;     // waves per workgroup in the down kernel
-constexpr float kLoScale = 2048.f;        // h = hi + lo / 2048 with hi, lo fp16
+constexpr int kWaves = 8;
+constexpr int kThreads = kWaves * 64;
+constexpr int kGuWin = 8;             // gate/up tiles a wave keeps in flight (rolling window)
+constexpr int kDownWin = 4;           // down tiles a wave keeps in flight
+constexpr uint32_t kSpinLimit = 1u << 22;
+constexpr uint32_t kMagic = 0x43004300u;      // bf16 pair (128, 128)
 
-__device__ inline h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ inline bf2 as_bf2(uint32_t u) { return __builtin_bit_cast(bf2, u); }
+__device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
-// The 8 codes of one 32-bit word as 4 fp16 pairs (codes 0-1, 2-3, 4-5, 6-7), exact.
-// 0x6400 is fp16 1024 with a zero mantissa: or-ing a code into mantissa bits 0-3 gives
-// 1024 + q, into bits 4-7 gives 1024 + 16 q.
-__device__ inline void unpack8(uint32_t w, h2 out[4]) {
-    const uint32_t magic = 0x64006400u;
-    const uint32_t t = w >> 8;
-    const h2 k1024 = {(_Float16)1024.f, (_Float16)1024.f};
-    const h2 k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
-    const h2 k64 = {(_Float16)64.f, (_Float16)64.f};
-    out[0] = as_h2((w & 0x000F000Fu) | magic) - k1024;
-    out[1] = as_h2((w & 0x00F000F0u) | magic) * k16th - k64;
-    out[2] = as_h2((t & 0x000F000Fu) | magic) - k1024;
-    out[3] = as_h2((t & 0x00F000F0u) | magic) * k16th - k64;
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
 }
 
-// acc += sum over the 32 codes held in `q` (4 words) of code * v, v = 16 consecutive fp16 pairs
-__device__ inline float dot32(u32x4 q, const h2 *__restrict__ v, float acc) {
+// acc += sum over the 32 codes in q of (128 + code) * v; v = 16 bf16 pairs (codes 2j, 2j+1)
+__device__ inline float dot32(u32x4 q, const uint32_t *__restrict__ v, float acc) {
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-        h2 c[4];
-        unpack8(w[d], c);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc = __builtin_amdgcn_fdot2(c[j], v[4 * d + j], acc, false);
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t c = ((w[d] >> (4 * j)) & 0x000F000Fu) | kMagic;
+            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf2(c), as_bf2(v[4 * d + j]), acc, false);
+        }
     }
     return acc;
 }
@@ -62,206 +75,403 @@ __device__ inline float wave_sum(float v) {
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
     return v;
 }
+__device__ inline double wave_sum_f64(double v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+__device__ inline double wave_max_f64(double v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmax(v, __shfl_xor(v, m, 64));
+    return v;
+}
 
-// Sum of g consecutive fp16 values (g in {32, 64, 128}), same result in every lane.
-__device__ inline float group_sum(const _Float16 *__restrict__ v, int g, int lane) {
+// Sum of g consecutive bf16 values (g in {32, 64, 128}), same value in every lane.
+__device__ inline float group_sum_bf16(const uint16_t *__restrict__ v, int g, int lane) {
     float s = 0.f;
-    for (int i = lane; i < g; i += 64) s += (float)v[i];
+    if (2 * lane < g) {
+        const uint32_t p = *reinterpret_cast<const uint32_t *>(v + 2 * lane);
+        s = bf16_lo(p) + bf16_hi(p);
+    }
     return wave_sum(s);
 }
-__device__ inline float group_sum_hilo(const _Float16 *__restrict__ hi, const _Float16 *__restrict__ lo,
-                                       int g, int lane) {
-    float s = 0.f;
-    for (int i = lane; i < g; i += 64) s += (float)hi[i] + (float)lo[i] * (1.f / kLoScale);
-    return wave_sum(s);
-}
 
-// Gate and up projections of one 64-row slice of the intermediate dimension for the (<= MT)
-// tokens of one expert, then h = silu(gate) * up, written as an fp16 hi/lo pair.
-// grid.x = I / 64, grid.y = routed experts of the call; block = 8 waves splitting K = H by groups.
-template <int MT>
-__global__ __launch_bounds__(kGuWaves * 64)
-void draft_gateup_kernel(const Plan *__restrict__ plan, int S, const _Float16 *__restrict__ xh,
-                         _Float16 *__restrict__ hh, _Float16 *__restrict__ hl, int H, int I, int g)
+struct FusedArgs {
+    const uint16_t *wr;         // [E,H] bf16
+    const float *bias;          // [E] or null
+    const char *q;              // int4 codes blobs
+    const char *sz;             // scale/zero blobs
+    size_t stride_q, stride_sz;
+    DraftSync *sync;            // counters, idle = 0
+    double *logits;             // [T,E] scratch
+    float *yacc;                // [T,H] accumulator, idle = 0
+    float *y;                   // [T,H] out
+    int32_t *ids_out;           // [T,k]
+    float *conf_out;            // [T,k] or null
+    Plan *plan;                 // filled for the shared-expert kernels when S > 0
+    const char *shared;         // bf16 shared expert blobs
+    size_t shared_stride;
+    int T, H, E, I, k, g, S, renorm;
+};
+
+template <int MT, int UPG>
+__global__ __launch_bounds__(kThreads, MT <= 2 ? 4 : 2)   // MT <= 2: 4 waves per SIMD, two workgroups per CU
+void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 {
-    const int u = S + blockIdx.y;
-    if (u >= plan->n_active) return;
-    const int cnt = plan->act_cnt[u];
-    const int off = plan->act_off[u];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int U = H / 32, G = H / g, upg = g / 32;
-    const size_t qmat = (size_t)(I / 64) * U * 64;            // 16-byte units per matrix
-    const size_t szmat = (size_t)(I / 64) * G * 64;           // 4-byte units per matrix
-    const u32x4 *qg = reinterpret_cast<const u32x4 *>(plan->act_w0[u]) + (size_t)blockIdx.x * U * 64 + lane;
-    const u32x4 *qu = qg + qmat;
-    const uint32_t *szg = reinterpret_cast<const uint32_t *>(plan->act_w1[u]) + (size_t)blockIdx.x * G * 64 + lane;
-    const uint32_t *szu = szg + szmat;
+    __shared__ double s_part[kWaves];
+    __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
+    __shared__ float s_w[MOE_MAX_ASSIGN];
+    __shared__ float s_conf[MOE_MAX_ASSIGN];
+    __shared__ unsigned long long s_mask[MOE_MAX_EXPERTS / 64];
+    __shared__ int32_t s_row_a[MT];             // assignment index of each row of this item
+    __shared__ int32_t s_cnt;
+    __shared__ int32_t s_flag;
+    __shared__ float s_red[kWaves][MT][64];
+    __shared__ uint32_t s_h[MT][2][16];          // [row][hi / lo][pair]
+    __shared__ float s_hsum[MT];
 
-    const _Float16 *xt[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) xt[m] = xh + (size_t)plan->row_tok[off + (m < cnt ? m : 0)] * H;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T = a.T, H = a.H, E = a.E, I = a.I, k = a.k, g = a.g;
+    const int n = T * k;
 
-    float tg[MT], tu[MT];
+    // ---- 1. router rows owned by this workgroup (fp64 accumulation of exact fp32 products)
+    for (int e = blockIdx.x; e < E; e += gridDim.x) {
+        const uint16_t *row = a.wr + (size_t)e * H;
+        for (int t = 0; t < T; ++t) {
+            const uint16_t *xt = xin + (size_t)t * H;
+            double acc = 0.0;
+            for (int c = tid; c < H / 8; c += kThreads) {
+                const u32x4 xv = *reinterpret_cast<const u32x4 *>(xt + c * 8);
+                const u32x4 wv = *reinterpret_cast<const u32x4 *>(row + c * 8);
+                const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w}, ws[4] = {wv.x, wv.y, wv.z, wv.w};
 #pragma unroll
-    for (int m = 0; m < MT; ++m) { tg[m] = 0.f; tu[m] = 0.f; }
-
-    const int g0 = (wave * G) / kGuWaves, g1 = ((wave + 1) * G) / kGuWaves;
-    for (int gi = g0; gi < g1; ++gi) {
-        float ag[MT], au[MT];
-#pragma unroll
-        for (int m = 0; m < MT; ++m) { ag[m] = 0.f; au[m] = 0.f; }
-        for (int uu = 0; uu < upg; ++uu) {
-            const int ku = gi * upg + uu;
-            const u32x4 a = __builtin_nontemporal_load(qg + (size_t)ku * 64);
-            const u32x4 b = __builtin_nontemporal_load(qu + (size_t)ku * 64);
-#pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                const h2 *xv = reinterpret_cast<const h2 *>(xt[m] + ku * 32);
-                ag[m] = dot32(a, xv, ag[m]);
-                au[m] = dot32(b, xv, au[m]);
+                for (int i = 0; i < 4; ++i) {
+                    acc += (double)(bf16_lo(xs[i]) * bf16_lo(ws[i]));     // bf16 x bf16 is exact in fp32
+                    acc += (double)(bf16_hi(xs[i]) * bf16_hi(ws[i]));
+                }
             }
+            acc = wave_sum_f64(acc);
+            if (lane == 0) s_part[wave] = acc;
+            __syncthreads();
+            if (tid == 0) {
+                double l = 0.0;
+                for (int w = 0; w < kWaves; ++w) l += s_part[w];
+                l += a.bias ? (double)a.bias[e] : 0.0;
+                __hip_atomic_store(&a.logits[(size_t)t * E + e], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
         }
-        const h2 sg = as_h2(szg[(size_t)gi * 64]), su = as_h2(szu[(size_t)gi * 64]);
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const float xs = group_sum(xt[m] + gi * g, g, lane);
-            tg[m] += (float)sg.x * (ag[m] - (float)sg.y * xs);
-            tu[m] += (float)su.x * (au[m] - (float)su.y * xs);
-        }
+        if (tid == 0)
+            __hip_atomic_fetch_add(&a.sync->route_count, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
 
-    __shared__ float s_red[kGuWaves][2][MT][64];
+    // ---- 2. wait for all E rows (bounded), then top-k per token: wave t takes tokens t, t+8, ...
+    if (tid == 0) {
+        uint32_t spins = 0;
+        while (__hip_atomic_load(&a.sync->route_count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)E &&
+               ++spins < kSpinLimit)
+            __builtin_amdgcn_s_sleep(1);
+        s_flag = spins < kSpinLimit ? 1 : 0;
+    }
+    if (tid < MOE_MAX_EXPERTS / 64) s_mask[tid] = 0ull;
+    __syncthreads();
+    const bool ok = s_flag != 0;
+
+    for (int t = wave; t < T && ok; t += kWaves) {
+        double l[4];
+        double mx = -INFINITY;
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        s_red[wave][0][m][lane] = tg[m];
-        s_red[wave][1][m][lane] = tu[m];
+        for (int i = 0; i < 4; ++i) {
+            const int e = lane + 64 * i;
+            l[i] = e < E ? __hip_atomic_load(&a.logits[(size_t)t * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                         : -INFINITY;
+            mx = fmax(mx, l[i]);
+        }
+        mx = wave_max_f64(mx);
+        double den = 0.0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (lane + 64 * i < E) den += exp(l[i] - mx);
+        den = wave_sum_f64(den);
+        unsigned taken = 0;
+        double sel_sum = 0.0, my_conf = 0.0;
+        int my_id = 0;
+        for (int j = 0; j < k; ++j) {
+            double bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = lane + 64 * i;
+                if (e < E && !((taken >> i) & 1) && (bi == 0x7fffffff || l[i] > bv)) { bv = l[i]; bi = e; }
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                const double ov = __shfl_xor(bv, m, 64);
+                const int oi = __shfl_xor(bi, m, 64);
+                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
+            }
+            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+            const double p = exp(bv - mx) / den;
+            sel_sum += p;
+            if (lane == j) { my_conf = p; my_id = bi; }
+        }
+        if (lane < k) {
+            s_ids[t * k + lane] = my_id;
+            s_conf[t * k + lane] = (float)my_conf;
+            s_w[t * k + lane] = a.renorm ? (float)(my_conf / sel_sum) : (float)my_conf;
+            atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
+        }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < MT * 64; i += kGuWaves * 64) {
-        const int m = i >> 6, r = i & 63;
-        if (m >= cnt) continue;
-        float gsum = 0.f, usum = 0.f;
-#pragma unroll
-        for (int w = 0; w < kGuWaves; ++w) { gsum += s_red[w][0][m][r]; usum += s_red[w][1][m][r]; }
-        const float un = plan->x_unscale[plan->row_tok[off + m]];
-        gsum *= un;
-        usum *= un;
-        const float h = gsum / (1.f + expf(-gsum)) * usum;
-        const _Float16 hi = (_Float16)h;
-        const _Float16 lo = (_Float16)((h - (float)hi) * kLoScale);
-        const size_t o = (size_t)(off + m) * I + blockIdx.x * 64 + r;
-        hh[o] = hi;
-        hl[o] = lo;
+
+    // ---- 3. this workgroup's item: the u-th distinct expert (ascending id), slice s
+    const int nslice = I / 32;
+    const int u = blockIdx.x / nslice, slice = blockIdx.x % nslice;
+    int expert = -1;
+    if (ok) {
+        int seen = 0;
+        for (int wd = 0; wd < MOE_MAX_EXPERTS / 64 && expert < 0; ++wd) {
+            unsigned long long mk = s_mask[wd];
+            const int pc = __popcll(mk);
+            if (u < seen + pc) {
+                for (int r = u - seen; r > 0; --r) mk &= mk - 1ull;
+                expert = wd * 64 + __ffsll((long long)mk) - 1;
+            }
+            seen += pc;
+        }
     }
-}
-
-// Down projection of one 64-row slice of the hidden dimension: part[split, row, r] =
-// row_w[row] * sum over this workgroup's share of K = I.  grid.x = H / 64, grid.y = routed
-// experts, grid.z = K-splits; block = 4 waves splitting the workgroup's share by groups.
-template <int MT>
-__global__ __launch_bounds__(kDownWaves * 64)
-void draft_down_kernel(const Plan *__restrict__ plan, int S, const _Float16 *__restrict__ hh,
-                       const _Float16 *__restrict__ hl, float *__restrict__ part,
-                       int H, int I, int g, int n_assign)
-{
-    const int u = S + blockIdx.y;
-    if (u >= plan->n_active) return;
-    const int cnt = plan->act_cnt[u];
-    const int off = plan->act_off[u];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int U = I / 32, G = I / g, upg = g / 32;
-    const size_t qmat = (size_t)(I / 64) * (H / 32) * 64;     // gate (and up) codes, 16-byte units
-    const size_t szmat = (size_t)(I / 64) * (H / g) * 64;     // gate (and up) scale-zero, 4-byte units
-    const u32x4 *qd = reinterpret_cast<const u32x4 *>(plan->act_w0[u]) + 2 * qmat + (size_t)blockIdx.x * U * 64 + lane;
-    const uint32_t *szd = reinterpret_cast<const uint32_t *>(plan->act_w1[u]) + 2 * szmat + (size_t)blockIdx.x * G * 64 + lane;
-
-    const _Float16 *hi[MT], *lo[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) {
-        const size_t r = (size_t)(off + (m < cnt ? m : 0)) * I;
-        hi[m] = hh + r;
-        lo[m] = hl + r;
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    if (expert >= 0 && wave == 0) {             // rows of the item: assignments with this expert, ascending
+        int cnt = 0;
+        for (int base = 0; base < n; base += 64) {
+            const int aidx = base + lane;
+            const bool hit = aidx < n && s_ids[aidx] == expert;
+            const unsigned long long b = __ballot(hit);
+            if (hit) {
+                const int pos = cnt + __popcll(b & ((1ull << lane) - 1ull));
+                if (pos < MT) s_row_a[pos] = aidx;
+            }
+            cnt += __popcll(b);
+        }
+        if (lane == 0) s_cnt = cnt < MT ? cnt : MT;
     }
-    float tot[MT];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) tot[m] = 0.f;
+    __syncthreads();
+    const int cnt = s_cnt;
 
-    const int nw = gridDim.z * kDownWaves;
-    const int wi = blockIdx.z * kDownWaves + wave;
-    const int g0 = (wi * G) / nw, g1 = ((wi + 1) * G) / nw;
-    for (int gi = g0; gi < g1; ++gi) {
-        float ah[MT], al[MT];
+    if (expert >= 0 && cnt > 0) {
+        const int U = H / 32, G = H / g;
+        const char *qb = a.q + (size_t)expert * a.stride_q;
+        const char *szb = a.sz + (size_t)expert * a.stride_sz;
+        // codes: [gate|up slices: (slice, ku, lane)] then [down: (slice, rt, lane)], 16 B per lane
+        const u32x4 *qgu = reinterpret_cast<const u32x4 *>(qb) + (size_t)slice * U * 64 + lane;
+        const u32x4 *qd = reinterpret_cast<const u32x4 *>(qb) + (size_t)nslice * U * 64 +
+                          (size_t)slice * (H / 64) * 64 + lane;
+        // scale/zero: [gate|up: (slice, group, lane)] then [down: (group of I, row of H)], 4 B each
+        const uint32_t *szgu = reinterpret_cast<const uint32_t *>(szb) + (size_t)slice * G * 64 + lane;
+        const uint32_t *szd = reinterpret_cast<const uint32_t *>(szb) + (size_t)nslice * G * 64 +
+                              (size_t)((slice * 32) / g) * H + lane;
+
+        int tok[MT];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) { ah[m] = 0.f; al[m] = 0.f; }
-        for (int uu = 0; uu < upg; ++uu) {
-            const int ku = gi * upg + uu;
-            const u32x4 a = __builtin_nontemporal_load(qd + (size_t)ku * 64);
+        for (int m = 0; m < MT; ++m)
+            tok[m] = MT == 1 ? __builtin_amdgcn_readfirstlane(s_row_a[0] / k) : __builtin_amdgcn_readfirstlane(s_row_a[m < cnt ? m : 0] / k);
+
+        // down tiles of this wave: row tiles wave, wave + 8, ...  Their loads do not depend on
+        // h, so the first window is requested before the gate/up work starts.
+        const int nrt = H / 64;
+        u32x4 dq[kDownWin];
+        uint32_t dsz[kDownWin];
 #pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                ah[m] = dot32(a, reinterpret_cast<const h2 *>(hi[m] + ku * 32), ah[m]);
-                al[m] = dot32(a, reinterpret_cast<const h2 *>(lo[m] + ku * 32), al[m]);
+        for (int i = 0; i < kDownWin; ++i) {
+            const int rt = wave + i * kWaves;
+            if (rt < nrt) {
+                dq[i] = __builtin_nontemporal_load(qd + (size_t)rt * 64);
+                dsz[i] = __builtin_nontemporal_load(szd + rt * 64);
             }
         }
-        const h2 sz = as_h2(szd[(size_t)gi * 64]);
+
+        // ---- gate / up: K = H split over the waves by groups; rolling window of kGuWin tiles
+        float tg[MT], acc[MT];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            const float hs = group_sum_hilo(hi[m] + gi * g, lo[m] + gi * g, g, lane);
-            tot[m] += (float)sz.x * (ah[m] + al[m] * (1.f / kLoScale) - (float)sz.y * hs);
+        for (int m = 0; m < MT; ++m) { tg[m] = 0.f; acc[m] = 0.f; }
+        const int u0 = ((wave * G) / kWaves) * UPG, u1 = (((wave + 1) * G) / kWaves) * UPG;
+        constexpr int kSzWin = kGuWin / UPG;
+        u32x4 gq[kGuWin];
+        uint32_t gsz[kSzWin];
+#pragma unroll
+        for (int i = 0; i < kGuWin; ++i)
+            if (u0 + i < u1) gq[i] = __builtin_nontemporal_load(qgu + (size_t)(u0 + i) * 64);
+#pragma unroll
+        for (int i = 0; i < kSzWin; ++i)
+            if (u0 + i * UPG < u1) gsz[i] = __builtin_nontemporal_load(szgu + (size_t)(u0 / UPG + i) * 64);
+        for (int base = u0; base < u1; base += kGuWin) {
+#pragma unroll
+            for (int i = 0; i < kGuWin; ++i) {
+                const int ku = base + i;
+                if (ku < u1) {
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        acc[m] = dot32(gq[i], reinterpret_cast<const uint32_t *>(xin + (size_t)tok[m] * H + ku * 32), acc[m]);
+                    if (ku + kGuWin < u1) gq[i] = __builtin_nontemporal_load(qgu + (size_t)(ku + kGuWin) * 64);
+                    if (i % UPG == UPG - 1) {                 // end of a group: apply scale / zero
+                        const int gi = ku / UPG;
+                        const uint32_t szv = gsz[i / UPG];
+                        if (ku + kGuWin < u1) gsz[i / UPG] = __builtin_nontemporal_load(szgu + (size_t)(gi + kSzWin) * 64);
+                        const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv & 0xffff));
+                        const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv >> 16)) + 128.f;
+#pragma unroll
+                        for (int m = 0; m < MT; ++m) {
+                            const float xs = group_sum_bf16(xin + (size_t)tok[m] * H + gi * g, g, lane);
+                            tg[m] += sc * (acc[m] - zp * xs);
+                            acc[m] = 0.f;
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) s_red[wave][m][lane] = tg[m];
+        __syncthreads();
+        // lanes 0-31 hold gate rows, 32-63 the matching up rows
+        for (int m = wave; m < cnt; m += kWaves) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) v += s_red[w][m][lane];
+            const float up = __shfl_down(v, 32, 64);
+            float h = v / (1.f + expf(-v)) * up;                 // meaningful in lanes 0..31
+            const uint16_t hi = f32_to_bf16_rne(h);
+            const float hif = __uint_as_float((uint32_t)hi << 16);
+            const uint16_t lo = f32_to_bf16_rne(h - hif);
+            const float rep = lane < 32 ? hif + __uint_as_float((uint32_t)lo << 16) : 0.f;
+            const float hs = wave_sum(rep);
+            const uint32_t hi_n = __shfl_down((uint32_t)hi, 1, 64), lo_n = __shfl_down((uint32_t)lo, 1, 64);
+            if (lane < 32 && !(lane & 1)) {
+                s_h[m][0][lane >> 1] = (uint32_t)hi | (hi_n << 16);
+                s_h[m][1][lane >> 1] = (uint32_t)lo | (lo_n << 16);
+            }
+            if (lane == 0) s_hsum[m] = hs;
+        }
+        __syncthreads();
+
+        // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns
+        float rw[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) rw[m] = s_w[s_row_a[m < cnt ? m : 0]];
+        for (int j0 = 0; wave + j0 * kWaves < nrt; j0 += kDownWin) {
+#pragma unroll
+            for (int i = 0; i < kDownWin; ++i) {
+                const int rt = wave + (j0 + i) * kWaves;
+                if (rt < nrt) {
+                    const u32x4 qv = dq[i];
+                    const uint32_t szv = dsz[i];
+                    const int rtn = rt + kDownWin * kWaves;
+                    if (rtn < nrt) {
+                        dq[i] = __builtin_nontemporal_load(qd + (size_t)rtn * 64);
+                        dsz[i] = __builtin_nontemporal_load(szd + rtn * 64);
+                    }
+                    const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv & 0xffff));
+                    const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv >> 16)) + 128.f;
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) {
+                        if (m < cnt) {
+                            float dacc = dot32(qv, s_h[m][0], 0.f);
+                            dacc = dot32(qv, s_h[m][1], dacc);
+                            const float val = sc * (dacc - zp * s_hsum[m]) * rw[m];
+                            __hip_atomic_fetch_add(&a.yacc[(size_t)tok[m] * H + rt * 64 + lane], val,
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+                }
+            }
         }
     }
 
-    __shared__ float s_red[kDownWaves][MT][64];
-#pragma unroll
-    for (int m = 0; m < MT; ++m) s_red[wave][m][lane] = tot[m];
+    // ---- 4. ticket; the last workgroup copies the accumulator out and restores the idle state
     __syncthreads();
-    for (int i = threadIdx.x; i < MT * 64; i += kDownWaves * 64) {
-        const int m = i >> 6, r = i & 63;
-        if (m >= cnt) continue;
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < kDownWaves; ++w) v += s_red[w][m][r];
-        part[((size_t)blockIdx.z * n_assign + off + m) * H + blockIdx.x * 64 + r] = v * plan->row_w[off + m];
+    if (tid == 0) {
+        __threadfence();
+        const uint32_t ticket = __hip_atomic_fetch_add(&a.sync->done_count, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_flag = (ticket == gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_flag) return;
+    __threadfence();
+    for (int i = tid; i < T * H; i += kThreads) {
+        const float v = __hip_atomic_load(&a.yacc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.y[i] = v;
+        a.yacc[i] = 0.f;
+    }
+    for (int i = tid; i < n; i += kThreads) {
+        a.ids_out[i] = ok ? s_ids[i] : -1;
+        if (a.conf_out) a.conf_out[i] = ok ? s_conf[i] : 0.f;
+    }
+    if (a.S > 0) {   // plan entries the shared-expert kernels and the final add read
+        Plan *p = a.plan;
+        for (int i = tid; i < n; i += kThreads) { p->perm[i] = i; p->row_live[i] = 0; }
+        for (int i = tid; i < a.S * T; i += kThreads) {
+            p->row_tok[n + i] = i % T;
+            p->row_w[n + i] = 1.f;
+            p->row_live[n + i] = 1;
+        }
+        if (tid < a.S) {
+            p->act_expert[tid] = E + tid;
+            p->act_off[tid] = n + tid * T;
+            p->act_cnt[tid] = T;
+            p->act_w0[tid] = (uint64_t)(a.shared + (size_t)tid * a.shared_stride);
+            p->act_w1[tid] = 0;
+        }
+        if (tid == 0) { p->n_active = a.S; p->n_routed_active = 0; p->n_rows = n + a.S * T; p->n_missing = 0; }
+    }
+    if (tid == 0) {
+        if (!ok) a.sync->error = 1u;
+        __hip_atomic_store(&a.sync->route_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.sync->done_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-template <int MT>
-void launch_gateup_t(const Shape &s, const Plan *plan, const void *xh, void *hh, void *hl, hipStream_t st)
+__global__ __launch_bounds__(256)
+void zero_kernel(uint32_t *p, size_t n)
 {
-    const int nexp = s.E < s.T * s.k ? s.E : s.T * s.k;
-    hipLaunchKernelGGL(draft_gateup_kernel<MT>, dim3(s.I / 64, nexp), dim3(kGuWaves * 64), 0, st, plan,
-                       s.S, (const _Float16 *)xh, (_Float16 *)hh, (_Float16 *)hl, s.H, s.I, s.g);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0u;
 }
 
 template <int MT>
-void launch_down_t(const Shape &s, const Plan *plan, const void *hh, const void *hl, float *part,
-                   hipStream_t st)
+void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st)
 {
-    const int nexp = s.E < s.T * s.k ? s.E : s.T * s.k;
-    hipLaunchKernelGGL(draft_down_kernel<MT>, dim3(s.H / 64, nexp, kDraftDownSplit), dim3(kDownWaves * 64),
-                       0, st, plan, s.S, (const _Float16 *)hh, (const _Float16 *)hl, part, s.H, s.I, s.g,
-                       s.T * s.k);
+    const int maxu = a.E < a.T * a.k ? a.E : a.T * a.k;
+    const dim3 grid(maxu * (a.I / 32)), block(kThreads);
+    if (a.g == 32) hipLaunchKernelGGL((draft_fused_kernel<MT, 1>), grid, block, 0, st, x, a);
+    else if (a.g == 64) hipLaunchKernelGGL((draft_fused_kernel<MT, 2>), grid, block, 0, st, x, a);
+    else hipLaunchKernelGGL((draft_fused_kernel<MT, 4>), grid, block, 0, st, x, a);
 }
 
 }  // namespace
 
-void launch_draft_gateup(const Shape &s, const Plan *plan, const void *xh, void *hh, void *hl,
-                         hipStream_t st)
+void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
 {
-    if (s.T <= 1) launch_gateup_t<1>(s, plan, xh, hh, hl, st);
-    else if (s.T <= 2) launch_gateup_t<2>(s, plan, xh, hh, hl, st);
-    else if (s.T <= 4) launch_gateup_t<4>(s, plan, xh, hh, hl, st);
-    else launch_gateup_t<8>(s, plan, xh, hh, hl, st);
+    FusedArgs a;
+    const uint16_t *x = (const uint16_t *)d.x;
+    a.wr = (const uint16_t *)d.wr; a.bias = d.bias;
+    a.q = (const char *)d.q; a.sz = (const char *)d.sz; a.stride_q = d.stride_q; a.stride_sz = d.stride_sz;
+    a.sync = d.sync; a.logits = d.logits; a.yacc = d.yacc; a.y = d.y;
+    a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
+    a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
+    a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;
+    if (s.T <= 1) launch_fused_t<1>(x, a, st);
+    else if (s.T <= 2) launch_fused_t<2>(x, a, st);
+    else if (s.T <= 4) launch_fused_t<4>(x, a, st);
+    else launch_fused_t<8>(x, a, st);
 }
 
-void launch_draft_down(const Shape &s, const Plan *plan, const void *hh, const void *hl,
-                       float *part, hipStream_t st)
+void launch_zero(void *p, size_t bytes, hipStream_t st)
 {
-    if (s.T <= 1) launch_down_t<1>(s, plan, hh, hl, part, st);
-    else if (s.T <= 2) launch_down_t<2>(s, plan, hh, hl, part, st);
-    else if (s.T <= 4) launch_down_t<4>(s, plan, hh, hl, part, st);
-    else launch_down_t<8>(s, plan, hh, hl, part, st);
+    const size_t n = bytes / 4;
+    int blocks = (int)((n + 255) / 256);
+    blocks = blocks > 1024 ? 1024 : (blocks < 1 ? 1 : blocks);
+    hipLaunchKernelGGL(zero_kernel, dim3(blocks), dim3(256), 0, st, (uint32_t *)p, n);
 }
 
 }  // namespace moespeq

@@ -32,27 +32,32 @@ struct Plan {
     int32_t row_tok[kMaxRows];        // token of a row
     float   row_w[kMaxRows];          // routing weight of a row (1 for shared)
     int32_t row_live[kMaxRows];       // 0: expert absent, the row's output must be skipped
-    float   x_unscale[MOE_MAX_TOKENS];   // draft: 1 / (power-of-two scale applied to x)
 };
 
 struct Shape {
     int T, H, E, I, k, S, g, renorm;
 };
 
-// Workspace carve-up (byte offsets from a 256-byte aligned base).
+// Cross-workgroup counters of the fused draft kernel.  Idle state: all zero.
+struct DraftSync {
+    uint32_t route_count;             // router rows published in the running call
+    uint32_t done_count;              // workgroups that have finished
+    uint32_t error;                   // sticky: a bounded wait ran out
+    uint32_t pad[61];
+};
+
+// Workspace carve-up (byte offsets from a 256-byte aligned base).  [sync, yacc) must be zero
+// between calls ("idle state"); moe_workspace_init establishes it, the draft kernel restores it.
 struct WsLayout {
-    // xh: fp16 x; hh/hl: fp16 hi/lo of h (int4 path); hb/hb_lo: bf16 h and its bf16 remainder
-    size_t plan, xh, hh, hl, hb, hb_lo, obuf, part, total;
+    // sync: DraftSync; yacc: fp32 [T,H] accumulator; logits: fp64 [T,E];
+    // hb / hb_lo: bf16 intermediate and its bf16 remainder; obuf: fp32 [rows,H] expert outputs
+    size_t sync, yacc, logits, plan, hb, hb_lo, obuf, total;
 };
 WsLayout ws_layout(const moe_layer_desc &d, int max_tokens);
 
-constexpr int kDraftDownSplit = 4;    // K-splits across workgroups in the int4 down kernel
-
 // route.hip
-// xh / x_unscale: optional fp16 copy of x scaled by a power of two per token (draft operand)
 void launch_route(const Shape &s, const void *x, const void *wr, const float *bias,
-                  int32_t *ids, float *w, float *conf, void *xh, float *x_unscale,
-                  hipStream_t st);
+                  int32_t *ids, float *w, float *conf, hipStream_t st);
 void launch_perm(const Shape &s, const int32_t *ids, int32_t *count, int32_t *off,
                  int32_t *perm, hipStream_t st);
 struct PlanArgs {
@@ -72,10 +77,15 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
                   int32_t *missing, int32_t *n_missing, hipStream_t st);
 
 // draft_int4.hip
-void launch_draft_gateup(const Shape &s, const Plan *plan, const void *xh, void *hh, void *hl,
-                         hipStream_t st);
-void launch_draft_down(const Shape &s, const Plan *plan, const void *hh, const void *hl,
-                       float *part, hipStream_t st);
+struct DraftFusedArgs {
+    const void *x, *wr; const float *bias;
+    const void *q, *sz; size_t stride_q, stride_sz;
+    DraftSync *sync; double *logits; float *yacc;
+    float *y; int32_t *ids_out; float *conf_out;
+    Plan *plan; const void *shared; size_t shared_stride;
+};
+void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
+void launch_zero(void *p, size_t bytes, hipStream_t st);
 
 // expert_bf16.hip
 // hb_lo != nullptr: the intermediate is kept as a bf16 hi + lo pair (draft-pass precision)

@@ -33,16 +33,13 @@ __device__ inline double wave_max_f64(double v) {
 }
 
 // One workgroup per token: logits of all experts (one wave per expert row at a time), then
-// wave 0 selects the top k and computes the softmax weights.  Optionally also writes the
-// token's activations as fp16 scaled by a power of two (draft pass operand).
+// wave 0 selects the top k and computes the softmax weights.
 __global__ __launch_bounds__(kRouteThreads)
 void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
                   const float *__restrict__ bias, int H, int E, int k, int renorm,
-                  int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf,
-                  _Float16 *__restrict__ xh, float *__restrict__ x_unscale)
+                  int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf)
 {
     __shared__ double s_logit[MOE_MAX_EXPERTS];
-    __shared__ float s_amax[kRouteThreads / 64];
     const int t = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nwave = kRouteThreads / 64;
@@ -67,31 +64,7 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
         if (lane == 0) s_logit[e] = acc + (bias ? (double)bias[e] : 0.0);
     }
 
-    if (xh) {   // power-of-two scaled fp16 copy of the activations
-        float amax = 0.f;
-        for (int h = threadIdx.x; h < H; h += kRouteThreads)
-            amax = fmaxf(amax, fabsf(__uint_as_float((uint32_t)xt[h] << 16)));
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
-        if (lane == 0) s_amax[wave] = amax;
-    }
     __syncthreads();
-    if (xh) {
-        float amax = 0.f;
-        for (int i = 0; i < nwave; ++i) amax = fmaxf(amax, s_amax[i]);
-        int sh = 0;                                   // scale = 2^sh puts amax in [2^14, 2^15)
-        if (amax > 0.f) {
-            int ex;
-            (void)frexpf(amax, &ex);                  // amax = m * 2^ex, m in [0.5, 1)
-            sh = 15 - ex;
-            sh = sh > 100 ? 100 : (sh < -100 ? -100 : sh);
-        }
-        const float scale = ldexpf(1.f, sh);
-        for (int h = threadIdx.x; h < H; h += kRouteThreads)
-            xh[(size_t)t * H + h] = (_Float16)(__uint_as_float((uint32_t)xt[h] << 16) * scale);
-        if (threadIdx.x == 0) x_unscale[t] = ldexpf(1.f, -sh);
-    }
-
     if (wave != 0) return;
     // each lane owns logits lane, lane + 64, lane + 128, lane + 192
     double l[4];
@@ -308,12 +281,11 @@ void union_kernel(const int32_t *__restrict__ ids, int n_ids, int E,
 }  // namespace
 
 void launch_route(const Shape &s, const void *x, const void *wr, const float *bias,
-                  int32_t *ids, float *w, float *conf, void *xh, float *x_unscale,
-                  hipStream_t st)
+                  int32_t *ids, float *w, float *conf, hipStream_t st)
 {
     hipLaunchKernelGGL(route_kernel, dim3(s.T), dim3(kRouteThreads), 0, st,
                        (const uint16_t *)x, (const uint16_t *)wr, bias, s.H, s.E, s.k, s.renorm,
-                       ids, w, conf, (_Float16 *)xh, x_unscale);
+                       ids, w, conf);
 }
 
 void launch_perm(const Shape &s, const int32_t *ids, int32_t *count, int32_t *off,

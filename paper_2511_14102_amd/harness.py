@@ -32,6 +32,7 @@ class DeviceLayer:
         self.q_bytes = B.int4_expert_q_bytes(self.desc)
         self.sz_bytes = B.int4_expert_sz_bytes(self.desc)
         self.workspace = torch.empty(B.workspace_bytes(self.desc, max_tokens), dtype=torch.uint8, device=dev)
+        ctx.workspace_init(self.workspace)
         self.max_tokens = max_tokens
 
         self.shared = None

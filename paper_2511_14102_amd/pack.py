@@ -1,5 +1,5 @@
 """Packers from row-major logical arrays to the kernel-native weight layouts documented in
-include/moespeq.h ("tile16x32" for bf16, "tile64x32" for int4 codes and scale/zero).
+include/moespeq.h ("tile16x32" for bf16, slice tiles for the int4 codes and scale/zero).
 
 Off the hot path: run once when weights are loaded.  Works on CPU or GPU torch tensors and
 returns flat uint8 tensors (byte images of the blobs)."""
@@ -26,31 +26,59 @@ def pack_bf16_expert(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor) -
 _NIBBLE_OF_CODE = [0, 4, 1, 5, 2, 6, 3, 7]
 
 
-def pack_int4_codes(q: torch.Tensor) -> torch.Tensor:
-    """[R, C] uint8 codes 0..15 -> bytes of the tile64x32 layout (R % 64 == 0, C % 32 == 0)."""
-    assert q.dtype == torch.uint8 and q.dim() == 2
+def _units(q: torch.Tensor) -> torch.Tensor:
+    """[R, C] uint8 codes -> [R, C/32, 16] uint8: the 16-byte unit of every 32 codes of a row."""
+    assert q.dtype == torch.uint8 and q.dim() == 2 and q.shape[1] % 32 == 0
     R, C = q.shape
-    assert R % 64 == 0 and C % 32 == 0
-    t = q.reshape(R // 64, 64, C // 32, 4, 8).to(torch.int64)      # [rt, lane, ku, word, code]
+    t = q.reshape(R, C // 32, 4, 8).to(torch.int64)                 # [row, unit, word, code]
     word = torch.zeros(t.shape[:-1], dtype=torch.int64, device=q.device)
     for n in range(8):
         word |= t[..., n] << (4 * _NIBBLE_OF_CODE[n])
-    word = word.permute(0, 2, 1, 3).contiguous()                   # [rt, ku, lane, word]
     b = torch.stack([(word >> (8 * i)) & 0xFF for i in range(4)], dim=-1).to(torch.uint8)
-    return b.reshape(-1)
+    return b.reshape(R, C // 32, 16)
 
 
-def pack_int4_sz(s: torch.Tensor, z: torch.Tensor) -> torch.Tensor:
-    """scale, zero [R, C/g] fp16 -> bytes: [R/64, C/g, 64 lanes, (s, z)]."""
+def pack_int4_gateup_codes(qg: torch.Tensor, qu: torch.Tensor) -> torch.Tensor:
+    """gate, up codes [I, H] -> tiles (slice, unit) of 64 lanes: 32 gate rows then the 32
+    matching up rows of the slice."""
+    I, H = qg.shape
+    assert qu.shape == (I, H) and I % 32 == 0
+    ug = _units(qg).reshape(I // 32, 32, H // 32, 16)
+    uu = _units(qu).reshape(I // 32, 32, H // 32, 16)
+    t = torch.cat([ug, uu], dim=1)                                   # [slice, lane, unit, 16]
+    return t.permute(0, 2, 1, 3).contiguous().reshape(-1)
+
+
+def pack_int4_down_codes(qd: torch.Tensor) -> torch.Tensor:
+    """down codes [H, I] -> tiles (slice of 32 input columns, row tile of 64 outputs)."""
+    H, I = qd.shape
+    assert H % 64 == 0 and I % 32 == 0
+    u = _units(qd).reshape(H // 64, 64, I // 32, 16)                 # [rt, lane, slice, 16]
+    return u.permute(2, 0, 1, 3).contiguous().reshape(-1)
+
+
+def _sz_pairs(s: torch.Tensor, z: torch.Tensor) -> torch.Tensor:
     assert s.dtype == torch.float16 and z.dtype == torch.float16 and s.shape == z.shape
-    R, G = s.shape
-    assert R % 64 == 0
-    t = torch.stack([s, z], dim=-1).reshape(R // 64, 64, G, 2).permute(0, 2, 1, 3).contiguous()
-    return t.view(torch.uint8).reshape(-1)
+    return torch.stack([s, z], dim=-1)                               # [..., 2] fp16
+
+
+def pack_int4_gateup_sz(sg, zg, su, zu) -> torch.Tensor:
+    """scale / zero [I, H/g] of gate and up -> entries (slice, group, lane)."""
+    I, G = sg.shape
+    pg = _sz_pairs(sg, zg).reshape(I // 32, 32, G, 2)
+    pu = _sz_pairs(su, zu).reshape(I // 32, 32, G, 2)
+    t = torch.cat([pg, pu], dim=1)                                   # [slice, lane, group, 2]
+    return t.permute(0, 2, 1, 3).contiguous().view(torch.uint8).reshape(-1)
+
+
+def pack_int4_down_sz(sd, zd) -> torch.Tensor:
+    """scale / zero [H, I/g] of down -> entries (group, row)."""
+    return _sz_pairs(sd, zd).permute(1, 0, 2).contiguous().view(torch.uint8).reshape(-1)
 
 
 def pack_int4_expert(q, s, z):
     """q, s, z: dicts gate/up/down of one expert -> (codes blob, scale-zero blob)."""
-    qb = torch.cat([pack_int4_codes(q[n]) for n in ("gate", "up", "down")])
-    sb = torch.cat([pack_int4_sz(s[n], z[n]) for n in ("gate", "up", "down")])
+    qb = torch.cat([pack_int4_gateup_codes(q["gate"], q["up"]), pack_int4_down_codes(q["down"])])
+    sb = torch.cat([pack_int4_gateup_sz(s["gate"], z["gate"], s["up"], z["up"]),
+                    pack_int4_down_sz(s["down"], z["down"])])
     return qb, sb

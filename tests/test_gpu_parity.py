@@ -100,10 +100,11 @@ def test_draft_layer(case):
     e = rel_err(to_np(r["y"]), ref["y"][:Tm])
     say("   rel err %.3e" % e)
     assert e <= TOL_DRAFT
-    # same call again: identical bits
+    # same call again: identical ids; y is summed with fp32 atomics, so only its last bits may move
     r2 = case.D.draft(x[:Tm].cuda())
     torch.cuda.synchronize()
-    assert torch.equal(r["y"], r2["y"]) and torch.equal(r["ids"], r2["ids"])
+    assert torch.equal(r["ids"], r2["ids"]) and torch.equal(r["conf"], r2["conf"])
+    assert rel_err(to_np(r2["y"]), to_np(r["y"])) <= 1e-5
 
 
 def test_verify_layer(case):

@@ -43,43 +43,60 @@ def test_bf16_tile16x32_layout_matches_the_header_formula():
             assert int(img[o]) | (int(img[o + 1]) << 8) == int(bits[r, c])
 
 
-def test_int4_tile64x32_layout_matches_the_header_formula():
+def _code_at(words, unit_index, lane, c):
+    """Code c (0..31) of the 16-byte unit owned by `lane` of tile `unit_index`."""
+    d, n = c // 8, c % 8
+    p = n // 2 if n % 2 == 0 else 4 + n // 2
+    return (int(words[(unit_index * 64 + lane) * 4 + d]) >> (4 * p)) & 15
+
+
+def test_int4_slice_layout_matches_the_header_formula():
     rng = np.random.default_rng(1)
-    R, C, g = 128, 96, 32
-    q = torch.from_numpy(rng.integers(0, 16, (R, C)).astype(np.uint8))
-    s = torch.from_numpy(rng.random((R, C // g)).astype(np.float16))
-    z = torch.from_numpy(rng.integers(0, 16, (R, C // g)).astype(np.float16))
-    img = pack.pack_int4_codes(q).numpy()
-    assert img.size == R * C // 2
-    words = img.view("<u4")
-    for r in range(R):
-        for c in range(C):
-            tile = (r // 64) * (C // 32) + c // 32
-            d, n = (c % 32) // 8, c % 8
-            p = n // 2 if n % 2 == 0 else 4 + n // 2
-            word = int(words[(tile * 64 + r % 64) * 4 + d])
-            assert (word >> (4 * p)) & 15 == int(q[r, c])
-    simg = pack.pack_int4_sz(s, z).numpy().view("<u2")
-    for r in range(R):
-        for gi in range(C // g):
-            i = ((r // 64) * (C // g) + gi) * 64 + r % 64
-            assert simg[2 * i] == s.numpy().view(np.uint16)[r, gi]
-            assert simg[2 * i + 1] == z.numpy().view(np.uint16)[r, gi]
+    H, I, g = 128, 96, 32
+    q = {n: torch.from_numpy(rng.integers(0, 16, shp).astype(np.uint8))
+         for n, shp in (("gate", (I, H)), ("up", (I, H)), ("down", (H, I)))}
+    s = {n: torch.from_numpy(rng.random((q[n].shape[0], q[n].shape[1] // g)).astype(np.float16)) for n in q}
+    z = {n: torch.from_numpy(rng.integers(0, 16, s[n].shape).astype(np.float16)) for n in q}
+    qb, sb = pack.pack_int4_expert(q, s, z)
+    assert qb.numel() == 3 * H * I // 2 and sb.numel() == 3 * H * I // g * 4
+    words = qb.numpy().view("<u4")
+    n_gu_tiles = (I // 32) * (H // 32)
+    for r in range(I):
+        for c in range(H):
+            sl, u = r // 32, c // 32
+            tile = sl * (H // 32) + u
+            assert _code_at(words, tile, r % 32, c % 32) == int(q["gate"][r, c])
+            assert _code_at(words, tile, 32 + r % 32, c % 32) == int(q["up"][r, c])
+    for r in range(H):
+        for c in range(I):
+            tile = n_gu_tiles + (c // 32) * (H // 64) + r // 64
+            assert _code_at(words, tile, r % 64, c % 32) == int(q["down"][r, c])
+    ent = sb.numpy().view("<u2").reshape(-1, 2)
+    G = H // g
+    bits = lambda t: t.numpy().view(np.uint16)
+    for r in range(I):
+        for gi in range(G):
+            i = ((r // 32) * G + gi) * 64 + r % 32
+            assert ent[i, 0] == bits(s["gate"])[r, gi] and ent[i, 1] == bits(z["gate"])[r, gi]
+            assert ent[i + 32, 0] == bits(s["up"])[r, gi] and ent[i + 32, 1] == bits(z["up"])[r, gi]
+    base = (I // 32) * G * 64
+    for r in range(H):
+        for gi in range(I // g):
+            i = base + gi * H + r
+            assert ent[i, 0] == bits(s["down"])[r, gi] and ent[i, 1] == bits(z["down"])[r, gi]
 
 
-def test_code_pairs_unpack_with_two_masks():
-    # the property the kernel relies on: (word & 0x000F000F) holds codes (0, 1),
-    # (word & 0x00F000F0) >> 4 codes (2, 3), and the same two masks on word >> 8 give (4..7)
-    q = torch.arange(16, dtype=torch.uint8).repeat(64, 2)[:, :32].contiguous()
-    q[:, 8:16] = torch.tensor([3, 14, 1, 7, 9, 0, 15, 6], dtype=torch.uint8)
-    words = pack.pack_int4_codes(q).numpy().view("<u4").reshape(64, 4)
-    for d in range(4):
-        w = int(words[5, d])
-        codes = [int(v) for v in q[5, 8 * d:8 * d + 8]]
-        t = w >> 8
-        got = [w & 0xF, (w >> 16) & 0xF, (w >> 4) & 0xF, (w >> 20) & 0xF,
-               t & 0xF, (t >> 16) & 0xF, (t >> 4) & 0xF, (t >> 20) & 0xF]
-        assert got == codes
+def test_code_pairs_unpack_with_one_mask():
+    # the property the kernel relies on: ((word >> 4j) & 0x000F000F) holds codes (2j, 2j+1)
+    q = torch.zeros((64, 32), dtype=torch.uint8)
+    q[5, 8:16] = torch.tensor([3, 14, 1, 7, 9, 0, 15, 6], dtype=torch.uint8)
+    words = pack.pack_int4_down_codes(q).numpy().view("<u4").reshape(64, 4)
+    w = int(words[5, 1])
+    got = []
+    for j in range(4):
+        m = (w >> (4 * j)) & 0x000F000F
+        got += [m & 0xF, (m >> 16) & 0xF]
+    assert got == [3, 14, 1, 7, 9, 0, 15, 6]
 
 
 def test_expert_blob_sizes_and_order():
