@@ -133,8 +133,9 @@ int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *byte
 
 /* Puts a workspace into its idle state (enqueues a fill kernel on `stream`; workspace_bytes a
  * multiple of 4).  Required once after allocation, before the first draft call: the draft
- * kernel keeps cross-workgroup counters and an fp32 accumulator there, which it expects zero
- * on entry and leaves zero on exit.  Nothing else is carried from call to call. */
+ * kernel exchanges the router result between its workgroups through tagged slots and a ticket
+ * counter there, which it expects zero on entry and leaves zero on exit (also when the call
+ * is replayed from a HIP graph).  Nothing else is carried from call to call. */
 int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- router: softmax + top-k, histogram, permutation --------------------------------- */

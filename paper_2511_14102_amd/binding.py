@@ -8,7 +8,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libmoespeq.so")
+_LIB_PATH = os.environ.get("MOESPEQ_LIB") or os.path.join(_HERE, "libmoespeq.so")
 _lib = None
 
 MOE_VERIFY_ACCUMULATE = 1

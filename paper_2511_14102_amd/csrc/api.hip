@@ -26,10 +26,8 @@ WsLayout ws_layout(const moe_layer_desc &d, int T)
     WsLayout L;
     const size_t n = (size_t)T * d.top_k, rows = n + (size_t)T * d.n_shared;
     size_t o = 0;
-    L.sync = o;   o += align256(sizeof(DraftSync));
-    // fixed sizes: the idle-state regions must sit at the same place whatever T a call uses
-    L.yacc = o;   o += align256((size_t)MOE_MAX_DRAFT_TOKENS * d.hidden * 4);
-    L.logits = o; o += align256((size_t)MOE_MAX_TOKENS * d.n_experts * 8);
+    L.tickets = o; o += 256;
+    L.slots = o;   o += align256((size_t)MOE_MAX_DRAFT_TOKENS * d.n_experts * 16);
     L.plan = o;   o += align256(sizeof(Plan));
     L.hb = o;     o += align256(rows * d.inter * 2);
     L.hb_lo = o;  o += align256(rows * d.inter * 2);
@@ -280,8 +278,8 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     a.x = x; a.wr = wr; a.bias = bias;
     a.q = routed->q; a.sz = routed->sz;
     a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
-    a.sync = (DraftSync *)(ws + L.sync); a.logits = (double *)(ws + L.logits);
-    a.yacc = (float *)(ws + L.yacc);
+    a.slots = (unsigned long long *)(ws + L.slots);
+    a.tickets = (uint32_t *)(ws + L.tickets);
     a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
     a.plan = plan; a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
     { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_fused(s, a, st); }

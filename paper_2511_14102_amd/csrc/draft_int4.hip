@@ -18,18 +18,22 @@
 // rows): its workgroup computes the 32 gate and 32 up pre-activations (one lane per row, K = H
 // split over the 8 waves), h = silu(gate) * up, and immediately multiplies h into the 32
 // matching columns of the down projection for all H outputs (one lane per output row),
-// adding the partial outputs into an fp32 accumulator with atomics.  Nothing but the router
-// result crosses workgroups before the end, so every weight byte can be requested as soon as
-// the expert ids are known.  The last workgroup to finish copies the accumulator to y and
-// clears it, so the workspace returns to its idle (all-zero) state.
+// adding the partial outputs into y with fp32 atomics.  Nothing but the router result crosses
+// workgroups, so every weight byte can be requested as soon as the expert ids are known, and
+// the kernel's end is the only completion point.
 //
-// Cross-workgroup protocol (bounded waits only):
-//   1. row e of the router is reduced by workgroup e (mod grid); it publishes logits[t][e] and
-//      increments route_count (release);
-//   2. every workgroup waits until route_count == E (acquire, bounded spin), then selects the
-//      top-k itself (identical in all workgroups);
-//   3. after its atomics every workgroup increments done_count (release); the one that draws the
-//      last ticket finalises.
+// Cross-workgroup protocol (one bounded wait, no cache flushes):
+//   1. router row e is reduced by workgroup e (mod grid), which first clears its share of y
+//      with agent-scope stores, waits for their completion, and then publishes the 16-byte
+//      slot {logit, tag = 1} of every token (logit first, tag after the logit has completed);
+//   2. every workgroup polls the slots with single 16-byte agent-scope loads until all are
+//      tagged, then selects the top-k itself (identical in all workgroups) and draws a ticket;
+//   3. y contributions are agent-scope atomics, which land after the clearing stores because
+//      the clearing completed before the slots were published;
+//   4. the workgroup holding the last ticket (everybody has finished polling by then) clears
+//      the tags and the ticket counter at its end, so the workspace is back in its idle state
+//      (tags and counter zero) when the kernel ends.  This also holds when the same launch is
+//      replayed from a HIP graph.
 #include "plan.h"
 
 namespace moespeq {
@@ -56,18 +60,35 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
+// (a & mask) | magic in one VALU op; mask is wave-uniform (an SGPR), magic sits in a VGPR
+__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(magic));
+    return r;
+}
+
 // acc += sum over the 32 codes in q of (128 + code) * v; v = 16 bf16 pairs (codes 2j, 2j+1)
 __device__ inline float dot32(u32x4 q, const uint32_t *__restrict__ v, float acc) {
+#ifdef MOE_DBG_NOCOMPUTE
+    return acc + __uint_as_float((q.x ^ q.y ^ q.z ^ q.w) & 0x3f800000u) * __uint_as_float(v[0] & 0x3f800000u);
+#endif
     const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t c = ((w[d] >> (4 * j)) & 0x000F000Fu) | kMagic;
-            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf2(c), as_bf2(v[4 * d + j]), acc, false);
+            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf2(and_or(w[d] >> (4 * j), 0x000F000Fu, kMagic)),
+                                                  as_bf2(v[4 * d + j]), acc, false);
         }
     }
     return acc;
+}
+
+// One 16-byte load at agent scope (served by the device's coherence point, not a stale cache line)
+__device__ inline u32x4 load16_agent(const void *p) {
+    u32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    return v;
 }
 
 __device__ inline float wave_sum(float v) {
@@ -102,10 +123,9 @@ struct FusedArgs {
     const char *q;              // int4 codes blobs
     const char *sz;             // scale/zero blobs
     size_t stride_q, stride_sz;
-    DraftSync *sync;            // counters, idle = 0
-    double *logits;             // [T,E] scratch
-    float *yacc;                // [T,H] accumulator, idle = 0
-    float *y;                   // [T,H] out
+    unsigned long long *slots;  // [T,E] x {logit bits, tag}; idle: tag = 0
+    uint32_t *tickets;          // idle: 0
+    float *y;                   // [T,H] out, accumulated with atomics
     int32_t *ids_out;           // [T,k]
     float *conf_out;            // [T,k] or null
     Plan *plan;                 // filled for the shared-expert kernels when S > 0
@@ -137,6 +157,13 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     const int n = T * k;
 
     // ---- 1. router rows owned by this workgroup (fp64 accumulation of exact fp32 products)
+#ifndef MOE_DBG_NOROUTE
+    if ((int)blockIdx.x < E) {
+        const int nprod = E < (int)gridDim.x ? E : (int)gridDim.x;
+        for (int i = blockIdx.x * kThreads + tid; i < T * H; i += nprod * kThreads)
+            __hip_atomic_store(&a.y[i], 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // the clearing stores have completed
+    }
     for (int e = blockIdx.x; e < E; e += gridDim.x) {
         const uint16_t *row = a.wr + (size_t)e * H;
         for (int t = 0; t < T; ++t) {
@@ -154,41 +181,54 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
             acc = wave_sum_f64(acc);
             if (lane == 0) s_part[wave] = acc;
-            __syncthreads();
+            __syncthreads();                                             // also: every thread's clearing is done
             if (tid == 0) {
                 double l = 0.0;
                 for (int w = 0; w < kWaves; ++w) l += s_part[w];
                 l += a.bias ? (double)a.bias[e] : 0.0;
-                __hip_atomic_store(&a.logits[(size_t)t * E + e], l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                unsigned long long *slot = a.slots + 2 * ((size_t)t * E + e);
+                __hip_atomic_store(slot, (unsigned long long)__double_as_longlong(l), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // logit completed before its nonce
+                __hip_atomic_store(slot + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __syncthreads();
         }
-        if (tid == 0)
-            __hip_atomic_fetch_add(&a.sync->route_count, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
-
-    // ---- 2. wait for all E rows (bounded), then top-k per token: wave t takes tokens t, t+8, ...
-    if (tid == 0) {
-        uint32_t spins = 0;
-        while (__hip_atomic_load(&a.sync->route_count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < (uint32_t)E &&
-               ++spins < kSpinLimit)
-            __builtin_amdgcn_s_sleep(1);
-        s_flag = spins < kSpinLimit ? 1 : 0;
-    }
+#endif
+    if (tid == 0) s_flag = 1;
     if (tid < MOE_MAX_EXPERTS / 64) s_mask[tid] = 0ull;
     __syncthreads();
-    const bool ok = s_flag != 0;
 
-    for (int t = wave; t < T && ok; t += kWaves) {
+    // ---- 2. wave t polls the slots of token t (bounded), then selects its top-k
+#ifdef MOE_DBG_NOROUTE
+    if (tid < n) { s_ids[tid] = tid % k; s_conf[tid] = 0.5f; s_w[tid] = 0.5f; atomicOr(&s_mask[0], 1ull << (tid % k)); }
+#else
+    for (int t = wave; t < T; t += kWaves) {
         double l[4];
+        {
+            uint32_t spins = 0;
+            bool all = false;
+            while (!all && ++spins < kSpinLimit) {
+                bool mine = true;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = lane + 64 * i;
+                    if (e < E) {
+                        const u32x4 v = load16_agent(a.slots + 2 * ((size_t)t * E + e));
+                        mine = mine && v.z == 1u;
+                        l[i] = __longlong_as_double((long long)(((unsigned long long)v.y << 32) | v.x));
+                    } else {
+                        l[i] = -INFINITY;
+                    }
+                }
+                all = __all(mine);
+                if (!all) __builtin_amdgcn_s_sleep(2);
+            }
+            if (!all) { if (lane == 0) s_flag = 0; continue; }
+        }
         double mx = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = lane + 64 * i;
-            l[i] = e < E ? __hip_atomic_load(&a.logits[(size_t)t * E + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                         : -INFINITY;
-            mx = fmax(mx, l[i]);
-        }
+        for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
         mx = wave_max_f64(mx);
         double den = 0.0;
 #pragma unroll
@@ -224,7 +264,14 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
         }
     }
+#endif
     __syncthreads();
+    const bool ok = s_flag != 0;
+    // this workgroup will not look at the slots again: draw a ticket (the result is needed
+    // only at the very end, so its latency is hidden behind the expert work)
+    uint32_t ticket = 0;
+    if (tid == 0)
+        ticket = __hip_atomic_fetch_add(a.tickets, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     // ---- 3. this workgroup's item: the u-th distinct expert (ascending id), slice s
     const int nslice = I / 32;
@@ -324,7 +371,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                         const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv >> 16)) + 128.f;
 #pragma unroll
                         for (int m = 0; m < MT; ++m) {
+#ifdef MOE_DBG_NOGSUM
+                            const float xs = 1.f;
+#else
                             const float xs = group_sum_bf16(xin + (size_t)tok[m] * H + gi * g, g, lane);
+#endif
                             tg[m] += sc * (acc[m] - zp * xs);
                             acc[m] = 0.f;
                         }
@@ -380,8 +431,12 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                             float dacc = dot32(qv, s_h[m][0], 0.f);
                             dacc = dot32(qv, s_h[m][1], dacc);
                             const float val = sc * (dacc - zp * s_hsum[m]) * rw[m];
-                            __hip_atomic_fetch_add(&a.yacc[(size_t)tok[m] * H + rt * 64 + lane], val,
+#ifdef MOE_DBG_NOATOMIC
+                            if (val == 123.456f) a.y[(size_t)tok[m] * H + rt * 64 + lane] = val;
+#else
+                            __hip_atomic_fetch_add(&a.y[(size_t)tok[m] * H + rt * 64 + lane], val,
                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
                         }
                     }
                 }
@@ -389,26 +444,22 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
 
-    // ---- 4. ticket; the last workgroup copies the accumulator out and restores the idle state
+    // ---- 4. last ticket: every workgroup has its logits, put the workspace back to idle
+    if (tid == 0) s_flag = (ticket == gridDim.x - 1) ? 1 : 0;
     __syncthreads();
-    if (tid == 0) {
-        __threadfence();
-        const uint32_t ticket = __hip_atomic_fetch_add(&a.sync->done_count, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_flag = (ticket == gridDim.x - 1) ? 1 : 0;
+    if (s_flag) {
+        for (int i = tid; i < T * E; i += kThreads)
+            __hip_atomic_store(a.slots + 2 * (size_t)i + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(a.tickets, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
-    if (!s_flag) return;
-    __threadfence();
-    for (int i = tid; i < T * H; i += kThreads) {
-        const float v = __hip_atomic_load(&a.yacc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        a.y[i] = v;
-        a.yacc[i] = 0.f;
-    }
+
+    // ---- 5. workgroup 0 reports the routing (and the plan the shared-expert kernels read)
+    if (blockIdx.x != 0) return;
     for (int i = tid; i < n; i += kThreads) {
         a.ids_out[i] = ok ? s_ids[i] : -1;
         if (a.conf_out) a.conf_out[i] = ok ? s_conf[i] : 0.f;
     }
-    if (a.S > 0) {   // plan entries the shared-expert kernels and the final add read
+    if (a.S > 0) {
         Plan *p = a.plan;
         for (int i = tid; i < n; i += kThreads) { p->perm[i] = i; p->row_live[i] = 0; }
         for (int i = tid; i < a.S * T; i += kThreads) {
@@ -424,11 +475,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             p->act_w1[tid] = 0;
         }
         if (tid == 0) { p->n_active = a.S; p->n_routed_active = 0; p->n_rows = n + a.S * T; p->n_missing = 0; }
-    }
-    if (tid == 0) {
-        if (!ok) a.sync->error = 1u;
-        __hip_atomic_store(&a.sync->route_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.sync->done_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -456,7 +502,7 @@ void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
     const uint16_t *x = (const uint16_t *)d.x;
     a.wr = (const uint16_t *)d.wr; a.bias = d.bias;
     a.q = (const char *)d.q; a.sz = (const char *)d.sz; a.stride_q = d.stride_q; a.stride_sz = d.stride_sz;
-    a.sync = d.sync; a.logits = d.logits; a.yacc = d.yacc; a.y = d.y;
+    a.slots = d.slots; a.tickets = d.tickets; a.y = d.y;
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
     a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;

@@ -38,20 +38,14 @@ struct Shape {
     int T, H, E, I, k, S, g, renorm;
 };
 
-// Cross-workgroup counters of the fused draft kernel.  Idle state: all zero.
-struct DraftSync {
-    uint32_t route_count;             // router rows published in the running call
-    uint32_t done_count;              // workgroups that have finished
-    uint32_t error;                   // sticky: a bounded wait ran out
-    uint32_t pad[61];
-};
-
-// Workspace carve-up (byte offsets from a 256-byte aligned base).  [sync, yacc) must be zero
-// between calls ("idle state"); moe_workspace_init establishes it, the draft kernel restores it.
+// Workspace carve-up (byte offsets from a 256-byte aligned base).  [tickets, plan) must be
+// zero between calls ("idle state"): moe_workspace_init establishes it, the draft kernel
+// restores it.  Their sizes do not depend on T, so the idle region is the same for every call.
 struct WsLayout {
-    // sync: DraftSync; yacc: fp32 [T,H] accumulator; logits: fp64 [T,E];
-    // hb / hb_lo: bf16 intermediate and its bf16 remainder; obuf: fp32 [rows,H] expert outputs
-    size_t sync, yacc, logits, plan, hb, hb_lo, obuf, total;
+    // tickets: one counter; slots: [MOE_MAX_DRAFT_TOKENS, E] x {fp64 logit, 64-bit tag} of the
+    // draft kernel's router exchange; hb / hb_lo: bf16 intermediate and its bf16 remainder;
+    // obuf: fp32 [rows,H] expert outputs
+    size_t tickets, slots, plan, hb, hb_lo, obuf, total;
 };
 WsLayout ws_layout(const moe_layer_desc &d, int max_tokens);
 
@@ -80,7 +74,7 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
 struct DraftFusedArgs {
     const void *x, *wr; const float *bias;
     const void *q, *sz; size_t stride_q, stride_sz;
-    DraftSync *sync; double *logits; float *yacc;
+    unsigned long long *slots; uint32_t *tickets;
     float *y; int32_t *ids_out; float *conf_out;
     Plan *plan; const void *shared; size_t shared_stride;
 };

@@ -311,3 +311,43 @@ def test_skew_all_tokens_same_experts(ctx):
     rd = c.D.draft(x.cuda())
     torch.cuda.synchronize()
     assert rel_err(to_np(rd["y"]), refd["y"]) <= TOL_DRAFT
+
+
+def test_graph_replays_match_eager_calls(ctx, tiny):
+    """A captured draft + union + verify step, replayed several times with new activations in
+    the static input buffer and eager work in between, must give what eager calls give."""
+    cfg = tiny.cfg
+    D = tiny.D
+    T, k, H = 4, cfg.top_k, cfg.hidden
+    xbuf = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+    yd = torch.empty((1, H), dtype=torch.float32, device="cuda")
+    idd = torch.empty((1, k), dtype=torch.int32, device="cuda")
+    cfd = torch.empty((1, k), dtype=torch.float32, device="cuda")
+    yv = torch.empty((T, H), dtype=torch.bfloat16, device="cuda")
+    idv = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    xbuf.copy_(synth.make_tokens(cfg, T, step=90).cuda())
+    D.draft(xbuf[:1], y=yd, ids=idd, conf=cfd)             # warm up outside capture
+    D.verify(xbuf, y=yv, ids=idv)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    say("graph: capture")
+    with torch.cuda.graph(g, stream=side):
+        D.draft(xbuf[:1], y=yd, ids=idd, conf=cfd)
+        D.verify(xbuf, y=yv, ids=idv)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        x = synth.make_tokens(cfg, T, step=91 + rep)
+        xbuf.copy_(x.cuda())
+        say("graph: replay", rep)
+        g.replay()
+        torch.cuda.synchronize()
+        got = (yd.clone(), idd.clone(), yv.clone(), idv.clone())
+        e_d = D.draft(x[:1].cuda())                        # eager work between replays
+        e_v = D.verify(x.cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(got[1], e_d["ids"]) and torch.equal(got[3], e_v["ids"])
+        assert rel_err(to_np(got[0]), to_np(e_d["y"])) <= 1e-5
+        assert torch.equal(got[2], e_v["y"])
+        ref = oracle_draft(tiny.A, x[:1])
+        assert np.array_equal(to_np(got[1]), ref["ids"]) and rel_err(to_np(got[0]), ref["y"]) <= TOL_DRAFT
