@@ -40,6 +40,8 @@ def main():
                     help="how the timed steps are launched (per-kernel timing always runs eagerly)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (known HBM traffic, for PMC scaling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -114,6 +116,14 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n_steps
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- eager timing
     ms_eager = timed(step, args.warmup, args.steps)
     log("eager: %.3f ms/step" % ms_eager)
@@ -153,26 +163,36 @@ def main():
     draft_bytes = k * int4_expert + S * 2 * P + E * H * 2 + H * 2 + H * 4          # one token
     mean_u_run = float(np.mean([uniq[(args.warmup + i) % n_layers] for i in range(args.steps)]))
     verify_bytes = mean_u_run * 2 * P + S * 2 * P + E * H * 2 + T * H * 4
-    gateup_bytes = (mean_u_run + S) * (2 * H * I * 2) + T * H * 2                   # dominant kernel
-    roofline = None
-    if "bf16_gateup_kernel" in kern:
-        # in draft calls of workloads with shared experts the same kernel also runs on S experts;
-        # phi has none, so every launch is a verify launch
-        kk = kern["bf16_gateup_kernel"]
-        if S == 0:
-            ach = gateup_bytes / (kk["us_avg"] * 1e-6) / 1e9
-            roofline = {"kernel": "bf16_gateup_kernel", "bound": "hbm", "achieved": round(ach, 1),
-                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                        "traffic": None, "bytes_per_launch": int(gateup_bytes),
-                        "us_per_launch": round(kk["us_avg"], 2)}
-    extra = {}
+    # per-launch algorithmic bytes of the three weight-streaming kernels (what the method must
+    # move: the selected experts' weights once, plus the small operands)
+    kbytes = {
+        "draft_fused_kernel": k * int4_expert + E * H * 2 + H * 2 + H * 4,
+        "bf16_gateup_kernel": (mean_u_run + S) * (2 * H * I * 2) + T * H * 2,
+        "bf16_down_kernel": (mean_u_run + S) * (H * I * 2) + T * k * I * 2,
+    }
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")   # HBM bytes per launch from committed PMC runs
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(cfg.name, {})
+        except Exception:
+            traffic = {}
+    roofline, extra = None, {}
     if kern:
-        df = kern.get("draft_fused_kernel")
-        if df:
-            extra["draft_fused_GBs"] = round((k * int4_expert + E * H * 2 + H * 6) / (df["us_avg"] * 1e-6) / 1e9, 1)
-        bd = kern.get("bf16_down_kernel")
-        if bd and S == 0:
-            extra["bf16_down_GBs"] = round(mean_u_run * H * I * 2 / (bd["us_avg"] * 1e-6) / 1e9, 1)
+        table = {}
+        for name, nbytes in kbytes.items():
+            kk = kern.get(name)
+            if not kk or (S > 0 and name != "draft_fused_kernel"):
+                continue        # with shared experts the bf16 kernels also run inside draft calls
+            ach = nbytes / (kk["us_avg"] * 1e-6) / 1e9
+            table[name] = {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                           "traffic": traffic.get(name), "bytes_per_launch": int(nbytes),
+                           "us_per_launch": round(kk["us_avg"], 2), "launches": kk["launches"],
+                           "ms_total": round(kk["ms_total"], 3)}
+        if table:
+            roofline = max(table.values(), key=lambda r: r["ms_total"])      # most time in the timed region
+            extra["kernels"] = table
         extra["kernel_us"] = {n: round(v["us_avg"], 2) for n, v in kern.items()}
 
     # ---- CPU baseline: the oracle on layer 0's step
@@ -181,21 +201,25 @@ def main():
         from oracle import oracle as orc
         from tests.common import oracle_arrays, oracle_draft, oracle_verify
         A = oracle_arrays(L0)
-        x0 = xs[0].cpu()
         tc = time.time()
-        oracle_draft(A, x0[:K])
-        oracle_verify(A, x0)
+        reps = 0
+        while time.time() - tc < 10.0 and reps < 64:         # bounded sample: >= 10 s of oracle work
+            x0 = synth.make_tokens(cfg, T, layer=0, step=reps)
+            oracle_draft(A, x0[:K])
+            oracle_verify(A, x0)
+            reps += 1
         dt = time.time() - tc
-        cpu = {"value": round((2 * K + 1) / dt, 3), "unit": "tokens/s", "cores": orc.num_threads(),
+        cpu = {"value": round(reps * (2 * K + 1) / dt, 3), "unit": "tokens/s", "cores": orc.num_threads(),
                "kind": "oracle", "seconds": round(dt, 2),
-               "sample": "one step of layer 0: %d draft tokens (int4) + one verify of %d tokens (bf16)" % (K, T)}
+               "sample": "%d steps of layer 0 (fresh tokens each): %d draft tokens (int4) + one verify of %d "
+                         "tokens (bf16) per step" % (reps, K, T)}
 
     tokens = 2 * K + 1
     out = {
-        "metric": "MoE-layer draft+verify tokens/s", "value": round(tokens / (ms_step * 1e-3), 1),
+        "metric": "MoE-layer draft+verify tokens/s and achieved HBM GB/s vs peak, 1 GPU", "value": round(tokens / (ms_step * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int4 draft + bf16 verify, fp32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": "int4+bf16 (fp32 accumulate)", "data": "synthetic",
         "config": {"workload": "%s-shaped MoE layer: H%d E%d I%d top%d g%d S%d, K=%d draft tokens + verify of %d, "
                                "%d distinct layers" % (cfg.name, H, E, I, k, g, S, K, T, n_layers),
                    "launch": launch, "tokens_per_step": tokens,
