@@ -27,7 +27,9 @@ WsLayout ws_layout(const moe_layer_desc &d, int T)
     const size_t n = (size_t)T * d.top_k, rows = n + (size_t)T * d.n_shared;
     size_t o = 0;
     L.tickets = o; o += 256;
-    L.slots = o;   o += align256((size_t)MOE_MAX_DRAFT_TOKENS * d.n_experts * 16);
+    // replicas are skewed by 256 bytes so that they do not all map to the same memory channel
+    L.slot_replica_bytes = align256((size_t)MOE_MAX_DRAFT_TOKENS * d.n_experts * 16) + 256;
+    L.slots = o;   o += kDraftSlotReplicas * L.slot_replica_bytes;
     L.plan = o;   o += align256(sizeof(Plan));
     L.hb = o;     o += align256(rows * d.inter * 2);
     L.hb_lo = o;  o += align256(rows * d.inter * 2);
@@ -279,6 +281,7 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     a.q = routed->q; a.sz = routed->sz;
     a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
     a.slots = (unsigned long long *)(ws + L.slots);
+    a.replica_stride = L.slot_replica_bytes / 8;
     a.tickets = (uint32_t *)(ws + L.tickets);
     a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
     a.plan = plan; a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);

@@ -25,7 +25,7 @@
 // Cross-workgroup protocol (one bounded wait, no cache flushes):
 //   1. router row e is reduced by workgroup e (mod grid), which first clears its share of y
 //      with agent-scope stores, waits for their completion, and then publishes the 16-byte
-//      slot {logit, tag = 1} of every token (logit first, tag after the logit has completed);
+//      slot {logit, tag = 1} of every token as one 16-byte store (in kReplicas copies);
 //   2. every workgroup polls the slots with single 16-byte agent-scope loads until all are
 //      tagged, then selects the top-k itself (identical in all workgroups) and draws a ticket;
 //   3. y contributions are agent-scope atomics, which land after the clearing stores because
@@ -46,8 +46,11 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kGuWin = 8;             // gate/up tiles a wave keeps in flight (rolling window)
-constexpr int kDownWin = 4;           // down tiles a wave keeps in flight
 constexpr uint32_t kSpinLimit = 1u << 22;
+// The router result is published in kReplicas copies; workgroup b polls copy b % kReplicas, so
+// that the polls of hundreds of workgroups do not all land on one address.
+constexpr int kReplicas = kDraftSlotReplicas;
+constexpr int kTicketGroups = 16;
 constexpr uint32_t kMagic = 0x43004300u;      // bf16 pair (128, 128)
 
 __device__ inline bf2 as_bf2(uint32_t u) { return __builtin_bit_cast(bf2, u); }
@@ -91,6 +94,10 @@ __device__ inline u32x4 load16_agent(const void *p) {
     return v;
 }
 
+__device__ inline void store16_agent(void *p, u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+
 __device__ inline float wave_sum(float v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
@@ -117,14 +124,22 @@ __device__ inline float group_sum_bf16(const uint16_t *__restrict__ v, int g, in
     return wave_sum(s);
 }
 
+#ifdef MOE_DBG_TIMING
+__device__ unsigned long long g_dbg_t[8192 * 8];
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_dbg_t[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define STAMP(i) do { } while (0)
+#endif
+
 struct FusedArgs {
     const uint16_t *wr;         // [E,H] bf16
     const float *bias;          // [E] or null
     const char *q;              // int4 codes blobs
     const char *sz;             // scale/zero blobs
     size_t stride_q, stride_sz;
-    unsigned long long *slots;  // [T,E] x {logit bits, tag}; idle: tag = 0
-    uint32_t *tickets;          // idle: 0
+    unsigned long long *slots;  // kReplicas x [T,E] x {logit bits, tag}; idle: tag = 0
+    size_t replica_stride;      // in 8-byte units
+    uint32_t *tickets;          // kTicketGroups + 1 counters; idle: 0
     float *y;                   // [T,H] out, accumulated with atomics
     int32_t *ids_out;           // [T,k]
     float *conf_out;            // [T,k] or null
@@ -150,12 +165,14 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     __shared__ uint32_t s_h[MT][2][16];          // [row][hi / lo][pair]
     __shared__ float s_hsum[MT];
 
+    constexpr int kDownWin = MT == 1 ? 8 : 4;    // down tiles a wave keeps in flight
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int T = a.T, H = a.H, E = a.E, I = a.I, k = a.k, g = a.g;
     const int n = T * k;
 
+    STAMP(0);
     // ---- 1. router rows owned by this workgroup (fp64 accumulation of exact fp32 products)
 #ifndef MOE_DBG_NOROUTE
     if ((int)blockIdx.x < E) {
@@ -182,19 +199,21 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             acc = wave_sum_f64(acc);
             if (lane == 0) s_part[wave] = acc;
             __syncthreads();                                             // also: every thread's clearing is done
-            if (tid == 0) {
+            if (tid < kReplicas) {                                       // thread r writes replica r
                 double l = 0.0;
                 for (int w = 0; w < kWaves; ++w) l += s_part[w];
                 l += a.bias ? (double)a.bias[e] : 0.0;
-                unsigned long long *slot = a.slots + 2 * ((size_t)t * E + e);
-                __hip_atomic_store(slot, (unsigned long long)__double_as_longlong(l), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // logit completed before its nonce
-                __hip_atomic_store(slot + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // {logit, tag} leaves as ONE aligned 16-byte agent-scope store and is read with one
+                // 16-byte load: a reader sees the tag only together with the logit
+                const unsigned long long lb = (unsigned long long)__double_as_longlong(l);
+                const u32x4 rec = {(uint32_t)lb, (uint32_t)(lb >> 32), 1u, 0u};
+                store16_agent(a.slots + (size_t)tid * a.replica_stride + 2 * ((size_t)t * E + e), rec);
             }
             __syncthreads();
         }
     }
 #endif
+    STAMP(1);
     if (tid == 0) s_flag = 1;
     if (tid < MOE_MAX_EXPERTS / 64) s_mask[tid] = 0ull;
     __syncthreads();
@@ -214,7 +233,8 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 for (int i = 0; i < 4; ++i) {
                     const int e = lane + 64 * i;
                     if (e < E) {
-                        const u32x4 v = load16_agent(a.slots + 2 * ((size_t)t * E + e));
+                        const u32x4 v = load16_agent(a.slots + (size_t)(blockIdx.x % kReplicas) * a.replica_stride +
+                                                     2 * ((size_t)t * E + e));
                         mine = mine && v.z == 1u;
                         l[i] = __longlong_as_double((long long)(((unsigned long long)v.y << 32) | v.x));
                     } else {
@@ -226,17 +246,20 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
             if (!all) { if (lane == 0) s_flag = 0; continue; }
         }
+        STAMP(7);
         double mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
         mx = wave_max_f64(mx);
-        double den = 0.0;
+        // the selection compares the fp64 logits; the softmax values only have to be good to
+        // fp32, so they are computed in fp32 from the fp64 differences
+        float den = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (lane + 64 * i < E) den += exp(l[i] - mx);
-        den = wave_sum_f64(den);
+            if (lane + 64 * i < E) den += expf((float)(l[i] - mx));
+        den = wave_sum(den);
         unsigned taken = 0;
-        double sel_sum = 0.0, my_conf = 0.0;
+        float sel_sum = 0.f, my_conf = 0.f;
         int my_id = 0;
         for (int j = 0; j < k; ++j) {
             double bv = -INFINITY;
@@ -253,26 +276,32 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
             }
             if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-            const double p = exp(bv - mx) / den;
+            const float p = expf((float)(bv - mx)) / den;
             sel_sum += p;
             if (lane == j) { my_conf = p; my_id = bi; }
         }
         if (lane < k) {
             s_ids[t * k + lane] = my_id;
-            s_conf[t * k + lane] = (float)my_conf;
-            s_w[t * k + lane] = a.renorm ? (float)(my_conf / sel_sum) : (float)my_conf;
+            s_conf[t * k + lane] = my_conf;
+            s_w[t * k + lane] = a.renorm ? my_conf / sel_sum : my_conf;
             atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
         }
     }
 #endif
     __syncthreads();
     const bool ok = s_flag != 0;
-    // this workgroup will not look at the slots again: draw a ticket (the result is needed
-    // only at the very end, so its latency is hidden behind the expert work)
-    uint32_t ticket = 0;
-    if (tid == 0)
-        ticket = __hip_atomic_fetch_add(a.tickets, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
+    // This workgroup will not look at the slots again: it draws a ticket.  The tickets are
+    // two-level (kTicketGroups first-level counters, then one) so that the returning atomics do
+    // not queue up on one address, and the atomic is issued by the last wave only after its
+    // first loads are in flight: memory results return in order, so a slow ticket would
+    // otherwise hold back that wave's weight loads (measured: up to 5 us with one counter).
+    uint32_t ticket = 0xffffffffu;
+    auto draw_ticket = [&]() {
+        if (tid == kThreads - 64)
+            ticket = __hip_atomic_fetch_add(a.tickets + blockIdx.x % kTicketGroups, 1u, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+    };
+    STAMP(2);
     // ---- 3. this workgroup's item: the u-th distinct expert (ascending id), slice s
     const int nslice = I / 32;
     const int u = blockIdx.x / nslice, slice = blockIdx.x % nslice;
@@ -326,6 +355,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         for (int m = 0; m < MT; ++m)
             tok[m] = MT == 1 ? __builtin_amdgcn_readfirstlane(s_row_a[0] / k) : __builtin_amdgcn_readfirstlane(s_row_a[m < cnt ? m : 0] / k);
 
+        STAMP(3);
         // down tiles of this wave: row tiles wave, wave + 8, ...  Their loads do not depend on
         // h, so the first window is requested before the gate/up work starts.
         const int nrt = H / 64;
@@ -354,6 +384,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
         for (int i = 0; i < kSzWin; ++i)
             if (u0 + i * UPG < u1) gsz[i] = __builtin_nontemporal_load(szgu + (size_t)(u0 / UPG + i) * 64);
+        draw_ticket();
         for (int base = u0; base < u1; base += kGuWin) {
 #pragma unroll
             for (int i = 0; i < kGuWin; ++i) {
@@ -383,6 +414,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 }
             }
         }
+        STAMP(4);
 #pragma unroll
         for (int m = 0; m < MT; ++m) s_red[wave][m][lane] = tg[m];
         __syncthreads();
@@ -407,6 +439,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
         __syncthreads();
 
+        STAMP(5);
         // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns
         float rw[MT];
 #pragma unroll
@@ -444,13 +477,29 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
 
+    else {
+        draw_ticket();
+    }
+    STAMP(6);
     // ---- 4. last ticket: every workgroup has its logits, put the workspace back to idle
-    if (tid == 0) s_flag = (ticket == gridDim.x - 1) ? 1 : 0;
+    if (tid == kThreads - 64) {
+        const uint32_t grp = blockIdx.x % kTicketGroups;
+        const uint32_t members = (gridDim.x - grp + kTicketGroups - 1) / kTicketGroups;
+        int last = 0;
+        if (ticket == members - 1) {                   // last of its group: second level
+            const uint32_t ngroups = gridDim.x < (uint32_t)kTicketGroups ? gridDim.x : (uint32_t)kTicketGroups;
+            const uint32_t t2 = __hip_atomic_fetch_add(a.tickets + kTicketGroups, 1u, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+            last = t2 == ngroups - 1;
+        }
+        s_flag = last;
+    }
     __syncthreads();
     if (s_flag) {
-        for (int i = tid; i < T * E; i += kThreads)
-            __hip_atomic_store(a.slots + 2 * (size_t)i + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (tid == 0) __hip_atomic_store(a.tickets, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int i = tid; i < T * E * kReplicas; i += kThreads)
+            __hip_atomic_store(a.slots + (size_t)(i / (T * E)) * a.replica_stride + 2 * (size_t)(i % (T * E)) + 1, 0ull,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid <= kTicketGroups) __hip_atomic_store(a.tickets + tid, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- 5. workgroup 0 reports the routing (and the plan the shared-expert kernels read)
@@ -502,7 +551,7 @@ void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
     const uint16_t *x = (const uint16_t *)d.x;
     a.wr = (const uint16_t *)d.wr; a.bias = d.bias;
     a.q = (const char *)d.q; a.sz = (const char *)d.sz; a.stride_q = d.stride_q; a.stride_sz = d.stride_sz;
-    a.slots = d.slots; a.tickets = d.tickets; a.y = d.y;
+    a.slots = d.slots; a.replica_stride = d.replica_stride; a.tickets = d.tickets; a.y = d.y;
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
     a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;
@@ -511,6 +560,13 @@ void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
     else if (s.T <= 4) launch_fused_t<4>(x, a, st);
     else launch_fused_t<8>(x, a, st);
 }
+
+#ifdef MOE_DBG_TIMING
+extern "C" int moe_debug_read_timing(void *out, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg_t), bytes);
+}
+#endif
 
 void launch_zero(void *p, size_t bytes, hipStream_t st)
 {

@@ -41,11 +41,13 @@ struct Shape {
 // Workspace carve-up (byte offsets from a 256-byte aligned base).  [tickets, plan) must be
 // zero between calls ("idle state"): moe_workspace_init establishes it, the draft kernel
 // restores it.  Their sizes do not depend on T, so the idle region is the same for every call.
+constexpr int kDraftSlotReplicas = 16;   // copies of the draft kernel's router-exchange slots
+
 struct WsLayout {
     // tickets: one counter; slots: [MOE_MAX_DRAFT_TOKENS, E] x {fp64 logit, 64-bit tag} of the
     // draft kernel's router exchange; hb / hb_lo: bf16 intermediate and its bf16 remainder;
     // obuf: fp32 [rows,H] expert outputs
-    size_t tickets, slots, plan, hb, hb_lo, obuf, total;
+    size_t tickets, slots, slot_replica_bytes, plan, hb, hb_lo, obuf, total;
 };
 WsLayout ws_layout(const moe_layer_desc &d, int max_tokens);
 
@@ -74,7 +76,7 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
 struct DraftFusedArgs {
     const void *x, *wr; const float *bias;
     const void *q, *sz; size_t stride_q, stride_sz;
-    unsigned long long *slots; uint32_t *tickets;
+    unsigned long long *slots; size_t replica_stride; uint32_t *tickets;
     float *y; int32_t *ids_out; float *conf_out;
     Plan *plan; const void *shared; size_t shared_stride;
 };
