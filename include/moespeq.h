@@ -40,21 +40,24 @@
  *      moe_bf16_expert_bytes() bytes.  One blob fills one slot of the expert cache.
  *
  *  int4 expert: codes q in 0..15, fp16 scale s and zero z per (row, group of g consecutive
- *  inputs), W = (q - z) * s.  32 codes of one row are a 16-byte unit = 4 little-endian 32-bit
- *  words; word d holds codes [8d, 8d + 8) of the unit; code number n of the word sits in bits
- *  [4p, 4p + 4) with p = n / 2 for even n and p = 4 + n / 2 for odd n (so `word & 0x000F000F`
- *  is the pair of codes 0, 1 and so on).  Units are grouped in 1 KiB tiles of 64 lanes:
+ *  inputs), W = (q - z) * s.  8 codes of one row (input columns 8j .. 8j + 7) are one
+ *  little-endian 32-bit word; code number n of the word sits in bits [4p, 4p + 4) with
+ *  p = n / 2 for even n and p = 4 + n / 2 for odd n (so `(word >> 4i) & 0x000F000F` is the pair
+ *  of codes 2i, 2i + 1).  Words are grouped in 1 KiB tiles of 64 lanes x 4 words in the register
+ *  image of a 16x16x32 MFMA operand: lane = chunk * 16 + r holds, for row block d = 0..3 (word d),
+ *  the word of row (d, r) and input chunk `chunk` (8 columns) of the tile's 32 columns.
  *    gate/up part ("slices" of 32 intermediate rows, I / 32 of them): tile (slice, u) for input
- *      unit u = c / 32 at index slice * (H / 32) + u; lane l < 32 is gate row 32 slice + l,
- *      lane l >= 32 is up row 32 slice + l - 32.
+ *      unit u = c / 32 at index slice * (H / 32) + u; row (d, r) is gate row 32 slice + 16 d + r
+ *      for d < 2 and up row 32 slice + 16 (d - 2) + r for d >= 2.
  *    down part, after the (I / 32) * (H / 32) gate/up tiles: tile (slice, rt) at index
- *      slice * (H / 64) + rt holds, in lane l, output row 64 rt + l, input columns
- *      [32 slice, 32 slice + 32).
+ *      slice * (H / 64) + rt; row (d, r) is output row 64 rt + 16 d + r, the 32 columns are
+ *      input columns [32 slice, 32 slice + 32).
  *    codes blob = moe_int4_expert_q_bytes() = 3 H I / 2 bytes.
- *  scale/zero blob: 4-byte entries (fp16 s in the low half, fp16 z in the high half):
- *    gate/up part: entry ((slice * (H / g) + group) * 64 + lane), lanes as above, group = c / g;
- *    down part, after the (I / 32) * (H / g) * 64 gate/up entries: entry (group * H + row),
- *      group = input column / g, row = output row.
+ *  scale/zero blob: 4-byte entries (fp16 s in the low half, fp16 z in the high half), four
+ *  consecutive entries d = 0..3 for each r:
+ *    gate/up part: entry ((slice * (H / g) + group) * 16 + r) * 4 + d, rows (d, r) as above;
+ *    down part, after the (I / 32) * (H / g) * 64 gate/up entries: entry
+ *      ((group * (H / 64) + rt) * 16 + r) * 4 + d, group = input column / g.
  *    moe_int4_expert_sz_bytes() = 3 H I / g * 4 bytes.
  */
 #ifndef MOESPEQ_H

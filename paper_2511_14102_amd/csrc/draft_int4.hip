@@ -10,17 +10,23 @@
 // Arithmetic.  W = (q - z) * s, so for one output row and one group G of inputs
 //     sum_{c in G} W[c] v[c] = s * ( sum_c (128 + q[c]) v[c]  -  (z + 128) * sum_c v[c] ).
 // 0x4300 is bf16 128.0 with a zero mantissa, so or-ing a code into mantissa bits 0-3 gives the
-// bf16 value 128 + q exactly: the inner loop is shift / and-or / bf16-pair dot product with fp32
-// accumulation; scale, zero and the 128 offset are applied once per group.  Activations stay
-// bf16 (exact); the SwiGLU intermediate is carried as a bf16 hi + lo pair (16 significant bits).
+// bf16 value 128 + q exactly: unpacking is one shift and one and-or per pair of codes.  The
+// products and sums are then done by the matrix cores (16x16x32 bf16 MFMA, fp32 accumulation):
+// the unpacked codes of 16 weight rows are the B operand, the activations of up to 16 tokens the
+// A operand.  With one token per call 15 of the 16 A rows are idle, but a plain VALU
+// dot-product loop was measured to be bound by the vector ALUs (about 60 VALU instructions per
+// KiB of codes), not by HBM; the matrix pipe takes the multiply-adds off them at no cost and
+// makes several tokens per call free.  Scale, zero and the 128 offset are applied once per
+// group on the accumulators.  Activations stay bf16 (exact); the SwiGLU intermediate is carried
+// as a bf16 hi + lo pair (16 significant bits, two MFMAs).
 //
 // Work decomposition ("slice fusion").  A work item is (expert, slice of 32 intermediate
-// rows): its workgroup computes the 32 gate and 32 up pre-activations (one lane per row, K = H
-// split over the 8 waves), h = silu(gate) * up, and immediately multiplies h into the 32
-// matching columns of the down projection for all H outputs (one lane per output row),
-// adding the partial outputs into y with fp32 atomics.  Nothing but the router result crosses
-// workgroups, so every weight byte can be requested as soon as the expert ids are known, and
-// the kernel's end is the only completion point.
+// rows): its workgroup computes the 32 gate and 32 up pre-activations (K = H split over the 8
+// waves by groups), h = silu(gate) * up, and immediately multiplies h into the 32 matching
+// columns of the down projection for all H outputs, adding the partial outputs into y with
+// fp32 atomics.  Nothing but the router result crosses workgroups, so every weight byte can be
+// requested as soon as the expert ids are known, and the kernel's end is the only completion
+// point.
 //
 // Cross-workgroup protocol (one bounded wait, no cache flushes):
 //   1. router row e is reduced by workgroup e (mod grid), which first clears its share of y
@@ -31,21 +37,20 @@
 //   3. y contributions are agent-scope atomics, which land after the clearing stores because
 //      the clearing completed before the slots were published;
 //   4. the workgroup holding the last ticket (everybody has finished polling by then) clears
-//      the tags and the ticket counter at its end, so the workspace is back in its idle state
-//      (tags and counter zero) when the kernel ends.  This also holds when the same launch is
-//      replayed from a HIP graph.
+//      the tags and the ticket counters at its end, so the workspace is back in its idle state
+//      when the kernel ends.  This also holds when the same launch is replayed from a HIP graph.
 #include "plan.h"
 
 namespace moespeq {
 
 namespace {
 
-typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr int kGuWin = 8;             // gate/up tiles a wave keeps in flight (rolling window)
 constexpr uint32_t kSpinLimit = 1u << 22;
 // The router result is published in kReplicas copies; workgroup b polls copy b % kReplicas, so
 // that the polls of hundreds of workgroups do not all land on one address.
@@ -53,7 +58,6 @@ constexpr int kReplicas = kDraftSlotReplicas;
 constexpr int kTicketGroups = 16;
 constexpr uint32_t kMagic = 0x43004300u;      // bf16 pair (128, 128)
 
-__device__ inline bf2 as_bf2(uint32_t u) { return __builtin_bit_cast(bf2, u); }
 __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
@@ -63,28 +67,31 @@ __device__ inline uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
-// (a & mask) | magic in one VALU op; mask is wave-uniform (an SGPR), magic sits in a VGPR
-__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(magic));
-    return r;
+// Unpack constants.  Both are made opaque to the compiler (one in a scalar, one in a vector
+// register) so that (a & mask) | magic has no literal operand and is selected as the single
+// instruction v_and_or_b32.  It must be the compiler's own instruction, not inline assembly:
+// the hazard recogniser does not see inline assembly as a VALU write, and an MFMA that read
+// such a result directly got a stale operand (wrong results on the GPU).
+struct UnpackConsts { uint32_t mask, magic; };
+__device__ inline UnpackConsts unpack_consts() {
+    UnpackConsts k = {0x000F000Fu, kMagic};
+    asm volatile("" : "+s"(k.mask));
+    asm volatile("" : "+v"(k.magic));
+    return k;
 }
 
-// acc += sum over the 32 codes in q of (128 + code) * v; v = 16 bf16 pairs (codes 2j, 2j+1)
-__device__ inline float dot32(u32x4 q, const uint32_t *__restrict__ v, float acc) {
-#ifdef MOE_DBG_NOCOMPUTE
-    return acc + __uint_as_float((q.x ^ q.y ^ q.z ^ q.w) & 0x3f800000u) * __uint_as_float(v[0] & 0x3f800000u);
-#endif
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            acc = __builtin_amdgcn_fdot2_f32_bf16(as_bf2(and_or(w[d] >> (4 * j), 0x000F000Fu, kMagic)),
-                                                  as_bf2(v[4 * d + j]), acc, false);
-        }
-    }
-    return acc;
+// The 8 codes of one 32-bit word as 8 bf16 values 128 + code, in code order (an MFMA operand)
+__device__ inline bf16x8 unpack8(uint32_t w, UnpackConsts k) {
+    u32x4 r;
+    r.x = (w & k.mask) | k.magic;
+    r.y = ((w >> 4) & k.mask) | k.magic;
+    r.z = ((w >> 8) & k.mask) | k.magic;
+    r.w = ((w >> 12) & k.mask) | k.magic;
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ inline f32x4 mfma(u32x4 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), b, c, 0, 0, 0);
 }
 
 // One 16-byte load at agent scope (served by the device's coherence point, not a stale cache line)
@@ -114,23 +121,6 @@ __device__ inline double wave_max_f64(double v) {
     return v;
 }
 
-// Sum of g consecutive bf16 values (g in {32, 64, 128}), same value in every lane.
-__device__ inline float group_sum_bf16(const uint16_t *__restrict__ v, int g, int lane) {
-    float s = 0.f;
-    if (2 * lane < g) {
-        const uint32_t p = *reinterpret_cast<const uint32_t *>(v + 2 * lane);
-        s = bf16_lo(p) + bf16_hi(p);
-    }
-    return wave_sum(s);
-}
-
-#ifdef MOE_DBG_TIMING
-__device__ unsigned long long g_dbg_t[8192 * 8];
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_dbg_t[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define STAMP(i) do { } while (0)
-#endif
-
 struct FusedArgs {
     const uint16_t *wr;         // [E,H] bf16
     const float *bias;          // [E] or null
@@ -149,32 +139,42 @@ struct FusedArgs {
     int T, H, E, I, k, g, S, renorm;
 };
 
+// MT: token capacity of the launch (1, 2, 4 or 8); UPG: 32-code units per group (g / 32).
 template <int MT, int UPG>
 __global__ __launch_bounds__(kThreads, MT <= 2 ? 4 : 2)   // MT <= 2: 4 waves per SIMD, two workgroups per CU
 void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 {
+    constexpr int NI = MT < 4 ? MT : 4;          // D rows (tokens) per lane that can be valid
+    constexpr int NC = MT > 4 ? 2 : 1;           // lane groups (of 16) whose D rows can be valid
+    // tiles a wave keeps in flight (rolling windows), sized so that no instantiation spills:
+    // two workgroups per CU leave 128 VGPRs per wave for MT <= 2
+    constexpr int kGuWin = MT == 1 ? (UPG == 4 ? 8 : 4) : (MT == 2 ? 4 : 8);
+    constexpr int kDownWin = MT == 1 && UPG == 4 ? 8 : 4;
+    constexpr int kInLoop = kDownWin < kGuWin / 2 ? kDownWin : kGuWin / 2;   // down tiles requested inside the last gate/up window
+    constexpr int kSzWin = kGuWin / UPG;
     __shared__ double s_part[kWaves];
     __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
     __shared__ float s_w[MOE_MAX_ASSIGN];
     __shared__ float s_conf[MOE_MAX_ASSIGN];
     __shared__ unsigned long long s_mask[MOE_MAX_EXPERTS / 64];
-    __shared__ int32_t s_row_a[MT];             // assignment index of each row of this item
+    __shared__ int32_t s_row_a[MT];             // assignment index of each row (token) of this item
     __shared__ int32_t s_cnt;
     __shared__ int32_t s_flag;
-    __shared__ float s_red[kWaves][MT][64];
-    __shared__ uint32_t s_h[MT][2][16];          // [row][hi / lo][pair]
+    __shared__ float s_red[kWaves][4][NI][NC * 16];   // [wave][row block][token in lane group][lane]
+    __shared__ __attribute__((aligned(16))) uint16_t s_hhi[MT][32], s_hlo[MT][32];
     __shared__ float s_hsum[MT];
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // x copy, then its group sums
 
-    constexpr int kDownWin = MT == 1 ? 8 : 4;    // down tiles a wave keeps in flight
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int T = a.T, H = a.H, E = a.E, I = a.I, k = a.k, g = a.g;
     const int n = T * k;
-
-    STAMP(0);
+    const int G = H / g;
+    const int xstride = H + 8;                   // bf16 elements per token in LDS (+16 B against bank conflicts)
+    uint16_t *s_x = reinterpret_cast<uint16_t *>(s_dyn);
+    float *s_xsum = reinterpret_cast<float *>(s_dyn + (size_t)MT * xstride * 2);   // [MT][G]
     // ---- 1. router rows owned by this workgroup (fp64 accumulation of exact fp32 products)
-#ifndef MOE_DBG_NOROUTE
     if ((int)blockIdx.x < E) {
         const int nprod = E < (int)gridDim.x ? E : (int)gridDim.x;
         for (int i = blockIdx.x * kThreads + tid; i < T * H; i += nprod * kThreads)
@@ -212,16 +212,28 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             __syncthreads();
         }
     }
-#endif
-    STAMP(1);
     if (tid == 0) s_flag = 1;
     if (tid < MOE_MAX_EXPERTS / 64) s_mask[tid] = 0ull;
     __syncthreads();
 
+    // ---- 1b. (while the router result travels) stage x in LDS and sum it per group
+    for (int i = tid; i < T * (H / 8); i += kThreads) {
+        const int t = i / (H / 8), c8 = i % (H / 8);
+        *reinterpret_cast<u32x4 *>(s_x + t * xstride + c8 * 8) = *reinterpret_cast<const u32x4 *>(xin + (size_t)t * H + c8 * 8);
+    }
+    __syncthreads();
+    for (int i = tid; i < T * G * 16; i += kThreads) {       // 16 threads per (token, group)
+        const int part = i & 15, tg_ = i >> 4;
+        const int t = tg_ / G, gi = tg_ % G;
+        const int per = g / 16;                               // 2, 4 or 8 values each
+        const uint16_t *src = s_x + t * xstride + gi * g + part * per;
+        float v = 0.f;
+        for (int j = 0; j < per; ++j) v += __uint_as_float((uint32_t)src[j] << 16);
+        v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64); v += __shfl_xor(v, 8, 64);
+        if (part == 0) s_xsum[t * G + gi] = v;
+    }
+
     // ---- 2. wave t polls the slots of token t (bounded), then selects its top-k
-#ifdef MOE_DBG_NOROUTE
-    if (tid < n) { s_ids[tid] = tid % k; s_conf[tid] = 0.5f; s_w[tid] = 0.5f; atomicOr(&s_mask[0], 1ull << (tid % k)); }
-#else
     for (int t = wave; t < T; t += kWaves) {
         double l[4];
         {
@@ -246,7 +258,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
             if (!all) { if (lane == 0) s_flag = 0; continue; }
         }
-        STAMP(7);
         double mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
@@ -287,7 +298,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
         }
     }
-#endif
     __syncthreads();
     const bool ok = s_flag != 0;
     // This workgroup will not look at the slots again: it draws a ticket.  The tickets are
@@ -301,7 +311,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             ticket = __hip_atomic_fetch_add(a.tickets + blockIdx.x % kTicketGroups, 1u, __ATOMIC_RELAXED,
                                             __HIP_MEMORY_SCOPE_AGENT);
     };
-    STAMP(2);
     // ---- 3. this workgroup's item: the u-th distinct expert (ascending id), slice s
     const int nslice = I / 32;
     const int u = blockIdx.x / nslice, slice = blockIdx.x % nslice;
@@ -338,138 +347,174 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     const int cnt = s_cnt;
 
     if (expert >= 0 && cnt > 0) {
-        const int U = H / 32, G = H / g;
+        const int U = H / 32;
+        const int r = lane & 15, c = lane >> 4;                  // MFMA lane coordinates
+        const UnpackConsts uk = unpack_consts();
         const char *qb = a.q + (size_t)expert * a.stride_q;
         const char *szb = a.sz + (size_t)expert * a.stride_sz;
-        // codes: [gate|up slices: (slice, ku, lane)] then [down: (slice, rt, lane)], 16 B per lane
+        // codes: [gate|up tiles (slice, ku)] then [down tiles (slice, rt)], 64 lanes x 16 B each
         const u32x4 *qgu = reinterpret_cast<const u32x4 *>(qb) + (size_t)slice * U * 64 + lane;
         const u32x4 *qd = reinterpret_cast<const u32x4 *>(qb) + (size_t)nslice * U * 64 +
                           (size_t)slice * (H / 64) * 64 + lane;
-        // scale/zero: [gate|up: (slice, group, lane)] then [down: (group of I, row of H)], 4 B each
-        const uint32_t *szgu = reinterpret_cast<const uint32_t *>(szb) + (size_t)slice * G * 64 + lane;
-        const uint32_t *szd = reinterpret_cast<const uint32_t *>(szb) + (size_t)nslice * G * 64 +
-                              (size_t)((slice * 32) / g) * H + lane;
+        // scale/zero: 16 B = the 4 row blocks' (s, z) of lane row r; [gate|up (slice, group)] then
+        // [down (group of I, rt)]
+        const u32x4 *szgu = reinterpret_cast<const u32x4 *>(szb) + (size_t)slice * G * 16 + r;
+        const u32x4 *szd = reinterpret_cast<const u32x4 *>(szb) + (size_t)nslice * G * 16 +
+                           (size_t)((slice * 32) / g) * (H / 64) * 16 + r;
 
-        int tok[MT];
+        // A-operand row of this lane: token slot r (slots >= cnt repeat slot 0; their D rows are ignored)
+        const int my_tok = s_row_a[r < cnt ? r : 0] / k;
+        const uint16_t *xrow = s_x + my_tok * xstride + c * 8;
+        // tokens whose results this lane holds in its D registers: slot 4c + i
+        int tok[NI];
+        float rw[NI];
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
-            tok[m] = MT == 1 ? __builtin_amdgcn_readfirstlane(s_row_a[0] / k) : __builtin_amdgcn_readfirstlane(s_row_a[m < cnt ? m : 0] / k);
-
-        STAMP(3);
-        // down tiles of this wave: row tiles wave, wave + 8, ...  Their loads do not depend on
-        // h, so the first window is requested before the gate/up work starts.
-        const int nrt = H / 64;
-        u32x4 dq[kDownWin];
-        uint32_t dsz[kDownWin];
-#pragma unroll
-        for (int i = 0; i < kDownWin; ++i) {
-            const int rt = wave + i * kWaves;
-            if (rt < nrt) {
-                dq[i] = __builtin_nontemporal_load(qd + (size_t)rt * 64);
-                dsz[i] = __builtin_nontemporal_load(szd + rt * 64);
-            }
+        for (int i = 0; i < NI; ++i) {
+            const int slot = 4 * c + i;
+            const int arow = s_row_a[slot < cnt ? slot : 0];
+            tok[i] = arow / k;
+            rw[i] = s_w[arow];
         }
 
+        // down tiles of this wave: row tiles wave, wave + 8, ...  Their loads do not depend on h:
+        // the codes are requested while the last gate/up window is consumed (taking over its
+        // registers, and queueing behind the gate/up data), the scales right after it.
+        const int nrt = H / 64;
+        u32x4 dq[kDownWin], dsz[kDownWin];
+
         // ---- gate / up: K = H split over the waves by groups; rolling window of kGuWin tiles
-        float tg[MT], acc[MT];
+        float tot[4][NI];
+        f32x4 acc[4];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) { tg[m] = 0.f; acc[m] = 0.f; }
+        for (int d = 0; d < 4; ++d) {
+            acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < NI; ++i) tot[d][i] = 0.f;
+        }
         const int u0 = ((wave * G) / kWaves) * UPG, u1 = (((wave + 1) * G) / kWaves) * UPG;
-        constexpr int kSzWin = kGuWin / UPG;
-        u32x4 gq[kGuWin];
-        uint32_t gsz[kSzWin];
+        u32x4 gq[kGuWin], gsz[kSzWin];
 #pragma unroll
         for (int i = 0; i < kGuWin; ++i)
             if (u0 + i < u1) gq[i] = __builtin_nontemporal_load(qgu + (size_t)(u0 + i) * 64);
 #pragma unroll
         for (int i = 0; i < kSzWin; ++i)
-            if (u0 + i * UPG < u1) gsz[i] = __builtin_nontemporal_load(szgu + (size_t)(u0 / UPG + i) * 64);
+            if (u0 + i * UPG < u1) gsz[i] = __builtin_nontemporal_load(szgu + (size_t)(u0 / UPG + i) * 16);
         draw_ticket();
+        u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (u0 < u1 ? u0 : 0) * 32);
+        bool down_issued = false;
         for (int base = u0; base < u1; base += kGuWin) {
+            const bool last = base + kGuWin >= u1;
 #pragma unroll
             for (int i = 0; i < kGuWin; ++i) {
                 const int ku = base + i;
+                if (last && (i & 1) && (i >> 1) < kInLoop) {
+                    const int rt = wave + (i >> 1) * kWaves;
+                    if (rt < nrt) dq[i >> 1] = __builtin_nontemporal_load(qd + (size_t)rt * 64);
+                }
                 if (ku < u1) {
-#pragma unroll
-                    for (int m = 0; m < MT; ++m)
-                        acc[m] = dot32(gq[i], reinterpret_cast<const uint32_t *>(xin + (size_t)tok[m] * H + ku * 32), acc[m]);
+                    const u32x4 qv = gq[i];
                     if (ku + kGuWin < u1) gq[i] = __builtin_nontemporal_load(qgu + (size_t)(ku + kGuWin) * 64);
-                    if (i % UPG == UPG - 1) {                 // end of a group: apply scale / zero
+                    const u32x4 xn = *reinterpret_cast<const u32x4 *>(xrow + (ku + 1 < u1 ? ku + 1 : ku) * 32);
+                    acc[0] = mfma(xa, unpack8(qv.x, uk), acc[0]);
+                    acc[1] = mfma(xa, unpack8(qv.y, uk), acc[1]);
+                    acc[2] = mfma(xa, unpack8(qv.z, uk), acc[2]);
+                    acc[3] = mfma(xa, unpack8(qv.w, uk), acc[3]);
+                    xa = xn;
+                    if (i % UPG == UPG - 1) {                 // end of a group: scale / zero / offset
                         const int gi = ku / UPG;
-                        const uint32_t szv = gsz[i / UPG];
-                        if (ku + kGuWin < u1) gsz[i / UPG] = __builtin_nontemporal_load(szgu + (size_t)(gi + kSzWin) * 64);
-                        const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv & 0xffff));
-                        const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv >> 16)) + 128.f;
+                        const u32x4 szv = gsz[i / UPG];
+                        if (ku + kGuWin < u1) gsz[i / UPG] = __builtin_nontemporal_load(szgu + (size_t)(gi + kSzWin) * 16);
+                        const uint32_t sw[4] = {szv.x, szv.y, szv.z, szv.w};
+                        float xs[NI];
 #pragma unroll
-                        for (int m = 0; m < MT; ++m) {
-#ifdef MOE_DBG_NOGSUM
-                            const float xs = 1.f;
-#else
-                            const float xs = group_sum_bf16(xin + (size_t)tok[m] * H + gi * g, g, lane);
-#endif
-                            tg[m] += sc * (acc[m] - zp * xs);
-                            acc[m] = 0.f;
+                        for (int j = 0; j < NI; ++j) xs[j] = s_xsum[tok[j] * G + gi];
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] & 0xffff));
+                            const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] >> 16)) + 128.f;
+#pragma unroll
+                            for (int j = 0; j < NI; ++j) tot[d][j] += sc * (acc[d][j] - zp * xs[j]);
+                            acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
                         }
                     }
                 }
             }
+            down_issued = last;
         }
-        STAMP(4);
 #pragma unroll
-        for (int m = 0; m < MT; ++m) s_red[wave][m][lane] = tg[m];
-        __syncthreads();
-        // lanes 0-31 hold gate rows, 32-63 the matching up rows
-        for (int m = wave; m < cnt; m += kWaves) {
-            float v = 0.f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) v += s_red[w][m][lane];
-            const float up = __shfl_down(v, 32, 64);
-            float h = v / (1.f + expf(-v)) * up;                 // meaningful in lanes 0..31
-            const uint16_t hi = f32_to_bf16_rne(h);
-            const float hif = __uint_as_float((uint32_t)hi << 16);
-            const uint16_t lo = f32_to_bf16_rne(h - hif);
-            const float rep = lane < 32 ? hif + __uint_as_float((uint32_t)lo << 16) : 0.f;
-            const float hs = wave_sum(rep);
-            const uint32_t hi_n = __shfl_down((uint32_t)hi, 1, 64), lo_n = __shfl_down((uint32_t)lo, 1, 64);
-            if (lane < 32 && !(lane & 1)) {
-                s_h[m][0][lane >> 1] = (uint32_t)hi | (hi_n << 16);
-                s_h[m][1][lane >> 1] = (uint32_t)lo | (lo_n << 16);
+        for (int i = 0; i < kDownWin; ++i) {
+            const int rt = wave + i * kWaves;
+            if (rt < nrt) {
+                if (!down_issued || i >= kInLoop) dq[i] = __builtin_nontemporal_load(qd + (size_t)rt * 64);
+                dsz[i] = __builtin_nontemporal_load(szd + (size_t)rt * 16);
             }
-            if (lane == 0) s_hsum[m] = hs;
+        }
+        if (c < NC) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+#pragma unroll
+                for (int i = 0; i < NI; ++i) s_red[wave][d][i][c * 16 + r] = tot[d][i];
+        }
+        __syncthreads();
+        // h for (token slot, row): row blocks 0, 1 are gate rows 0-15, 16-31; 2, 3 the matching up rows
+        for (int idx = tid; idx < 2 * NI * NC * 16; idx += kThreads) {
+            const int lr = idx % (NC * 16), i = (idx / (NC * 16)) % NI, d = idx / (NC * 16 * NI);
+            const int slot = 4 * (lr >> 4) + i;
+            if (slot < cnt) {
+                float gsum = 0.f, usum = 0.f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) { gsum += s_red[w][d][i][lr]; usum += s_red[w][d + 2][i][lr]; }
+                const float h = gsum / (1.f + expf(-gsum)) * usum;
+                const uint16_t hi = f32_to_bf16_rne(h);
+                const uint16_t lo = f32_to_bf16_rne(h - __uint_as_float((uint32_t)hi << 16));
+                s_hhi[slot][d * 16 + (lr & 15)] = hi;
+                s_hlo[slot][d * 16 + (lr & 15)] = lo;
+            }
+        }
+        __syncthreads();
+        if (tid < cnt) {                         // sum of the represented h over the slice, per token
+            float hs = 0.f;
+            for (int j = 0; j < 32; ++j)
+                hs += __uint_as_float((uint32_t)s_hhi[tid][j] << 16) + __uint_as_float((uint32_t)s_hlo[tid][j] << 16);
+            s_hsum[tid] = hs;
         }
         __syncthreads();
 
-        STAMP(5);
         // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns
-        float rw[MT];
+        const int hslot = r < cnt ? r : 0;
+        const u32x4 ha_hi = *reinterpret_cast<const u32x4 *>(&s_hhi[hslot][c * 8]);
+        const u32x4 ha_lo = *reinterpret_cast<const u32x4 *>(&s_hlo[hslot][c * 8]);
+        float hsum[NI];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) rw[m] = s_w[s_row_a[m < cnt ? m : 0]];
+        for (int i = 0; i < NI; ++i) hsum[i] = s_hsum[4 * c + i < cnt ? 4 * c + i : 0];
         for (int j0 = 0; wave + j0 * kWaves < nrt; j0 += kDownWin) {
 #pragma unroll
             for (int i = 0; i < kDownWin; ++i) {
                 const int rt = wave + (j0 + i) * kWaves;
                 if (rt < nrt) {
-                    const u32x4 qv = dq[i];
-                    const uint32_t szv = dsz[i];
+                    const u32x4 qv = dq[i], szv = dsz[i];
                     const int rtn = rt + kDownWin * kWaves;
                     if (rtn < nrt) {
                         dq[i] = __builtin_nontemporal_load(qd + (size_t)rtn * 64);
-                        dsz[i] = __builtin_nontemporal_load(szd + rtn * 64);
+                        dsz[i] = __builtin_nontemporal_load(szd + (size_t)rtn * 16);
                     }
-                    const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv & 0xffff));
-                    const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(szv >> 16)) + 128.f;
+                    const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, sw[4] = {szv.x, szv.y, szv.z, szv.w};
 #pragma unroll
-                    for (int m = 0; m < MT; ++m) {
-                        if (m < cnt) {
-                            float dacc = dot32(qv, s_h[m][0], 0.f);
-                            dacc = dot32(qv, s_h[m][1], dacc);
-                            const float val = sc * (dacc - zp * s_hsum[m]) * rw[m];
-#ifdef MOE_DBG_NOATOMIC
-                            if (val == 123.456f) a.y[(size_t)tok[m] * H + rt * 64 + lane] = val;
-#else
-                            __hip_atomic_fetch_add(&a.y[(size_t)tok[m] * H + rt * 64 + lane], val,
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#endif
+                    for (int d = 0; d < 4; ++d) {
+                        const bf16x8 b = unpack8(qw[d], uk);
+                        f32x4 o = mfma(ha_hi, b, (f32x4){0.f, 0.f, 0.f, 0.f});
+                        o = mfma(ha_lo, b, o);
+                        const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] & 0xffff));
+                        const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] >> 16)) + 128.f;
+                        if (c < NC) {
+#pragma unroll
+                            for (int j = 0; j < NI; ++j) {
+                                if (4 * c + j < cnt) {
+                                    const float val = sc * (o[j] - zp * hsum[j]) * rw[j];
+                                    __hip_atomic_fetch_add(&a.y[(size_t)tok[j] * H + rt * 64 + d * 16 + r], val,
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                }
+                            }
                         }
                     }
                 }
@@ -480,7 +525,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     else {
         draw_ticket();
     }
-    STAMP(6);
     // ---- 4. last ticket: every workgroup has its logits, put the workspace back to idle
     if (tid == kThreads - 64) {
         const uint32_t grp = blockIdx.x % kTicketGroups;
@@ -533,14 +577,29 @@ void zero_kernel(uint32_t *p, size_t n)
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = 0u;
 }
 
+// Launch with `lds` bytes of dynamic LDS; beyond 48 KiB the limit has to be raised once per kernel.
+template <typename K>
+void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, const uint16_t *x,
+                     const FusedArgs &a)
+{
+    static size_t raised = 0;                    // per instantiation
+    if (lds > 48 * 1024 && lds > raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        raised = lds;
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, x, a);
+}
+
 template <int MT>
 void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st)
 {
     const int maxu = a.E < a.T * a.k ? a.E : a.T * a.k;
     const dim3 grid(maxu * (a.I / 32)), block(kThreads);
-    if (a.g == 32) hipLaunchKernelGGL((draft_fused_kernel<MT, 1>), grid, block, 0, st, x, a);
-    else if (a.g == 64) hipLaunchKernelGGL((draft_fused_kernel<MT, 2>), grid, block, 0, st, x, a);
-    else hipLaunchKernelGGL((draft_fused_kernel<MT, 4>), grid, block, 0, st, x, a);
+    // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums
+    const size_t lds = (size_t)MT * (a.H + 8) * 2 + (size_t)MT * (a.H / a.g) * 4;
+    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1>, grid, block, lds, st, x, a);
+    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2>, grid, block, lds, st, x, a);
+    else launch_with_lds(draft_fused_kernel<MT, 4>, grid, block, lds, st, x, a);
 }
 
 }  // namespace
@@ -560,13 +619,6 @@ void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
     else if (s.T <= 4) launch_fused_t<4>(x, a, st);
     else launch_fused_t<8>(x, a, st);
 }
-
-#ifdef MOE_DBG_TIMING
-extern "C" int moe_debug_read_timing(void *out, size_t bytes)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_dbg_t), bytes);
-}
-#endif
 
 void launch_zero(void *p, size_t bytes, hipStream_t st)
 {

@@ -38,23 +38,30 @@ def _units(q: torch.Tensor) -> torch.Tensor:
     return b.reshape(R, C // 32, 16)
 
 
+def _dwords(q: torch.Tensor) -> torch.Tensor:
+    """[R, C] codes -> [R, C/32, 4, 4] uint8: row, 32-code unit, 8-code chunk c, the chunk's 4 bytes."""
+    R, C = q.shape
+    return _units(q).reshape(R, C // 32, 4, 4)
+
+
 def pack_int4_gateup_codes(qg: torch.Tensor, qu: torch.Tensor) -> torch.Tensor:
-    """gate, up codes [I, H] -> tiles (slice, unit) of 64 lanes: 32 gate rows then the 32
-    matching up rows of the slice."""
+    """gate, up codes [I, H] -> tiles (slice, unit): lane = chunk * 16 + r, word d = row block
+    (gate rows 0-15, gate rows 16-31, up rows 0-15, up rows 16-31 of the slice)."""
     I, H = qg.shape
     assert qu.shape == (I, H) and I % 32 == 0
-    ug = _units(qg).reshape(I // 32, 32, H // 32, 16)
-    uu = _units(qu).reshape(I // 32, 32, H // 32, 16)
-    t = torch.cat([ug, uu], dim=1)                                   # [slice, lane, unit, 16]
-    return t.permute(0, 2, 1, 3).contiguous().reshape(-1)
+    dg = _dwords(qg).reshape(I // 32, 2, 16, H // 32, 4, 4)          # [slice, half, r, unit, chunk, 4B]
+    du = _dwords(qu).reshape(I // 32, 2, 16, H // 32, 4, 4)
+    t = torch.cat([dg, du], dim=1)                                    # [slice, d, r, unit, chunk, 4B]
+    return t.permute(0, 3, 4, 2, 1, 5).contiguous().reshape(-1)      # [slice, unit, chunk, r, d, 4B]
 
 
 def pack_int4_down_codes(qd: torch.Tensor) -> torch.Tensor:
-    """down codes [H, I] -> tiles (slice of 32 input columns, row tile of 64 outputs)."""
+    """down codes [H, I] -> tiles (slice of 32 input columns, row tile of 64 outputs): lane =
+    chunk * 16 + r, word d = rows 16 d + r of the row tile."""
     H, I = qd.shape
     assert H % 64 == 0 and I % 32 == 0
-    u = _units(qd).reshape(H // 64, 64, I // 32, 16)                 # [rt, lane, slice, 16]
-    return u.permute(2, 0, 1, 3).contiguous().reshape(-1)
+    t = _dwords(qd).reshape(H // 64, 4, 16, I // 32, 4, 4)           # [rt, d, r, slice, chunk, 4B]
+    return t.permute(3, 0, 4, 2, 1, 5).contiguous().reshape(-1)      # [slice, rt, chunk, r, d, 4B]
 
 
 def _sz_pairs(s: torch.Tensor, z: torch.Tensor) -> torch.Tensor:
@@ -63,17 +70,19 @@ def _sz_pairs(s: torch.Tensor, z: torch.Tensor) -> torch.Tensor:
 
 
 def pack_int4_gateup_sz(sg, zg, su, zu) -> torch.Tensor:
-    """scale / zero [I, H/g] of gate and up -> entries (slice, group, lane)."""
+    """scale / zero [I, H/g] of gate and up -> entries (slice, group, r, d), d as for the codes."""
     I, G = sg.shape
-    pg = _sz_pairs(sg, zg).reshape(I // 32, 32, G, 2)
-    pu = _sz_pairs(su, zu).reshape(I // 32, 32, G, 2)
-    t = torch.cat([pg, pu], dim=1)                                   # [slice, lane, group, 2]
-    return t.permute(0, 2, 1, 3).contiguous().view(torch.uint8).reshape(-1)
+    pg = _sz_pairs(sg, zg).reshape(I // 32, 2, 16, G, 2)
+    pu = _sz_pairs(su, zu).reshape(I // 32, 2, 16, G, 2)
+    t = torch.cat([pg, pu], dim=1)                                   # [slice, d, r, group, 2]
+    return t.permute(0, 3, 2, 1, 4).contiguous().view(torch.uint8).reshape(-1)
 
 
 def pack_int4_down_sz(sd, zd) -> torch.Tensor:
-    """scale / zero [H, I/g] of down -> entries (group, row)."""
-    return _sz_pairs(sd, zd).permute(1, 0, 2).contiguous().view(torch.uint8).reshape(-1)
+    """scale / zero [H, I/g] of down -> entries (group, rt, r, d)."""
+    H, G = sd.shape
+    t = _sz_pairs(sd, zd).reshape(H // 64, 4, 16, G, 2)              # [rt, d, r, group, 2]
+    return t.permute(3, 0, 2, 1, 4).contiguous().view(torch.uint8).reshape(-1)
 
 
 def pack_int4_expert(q, s, z):

@@ -1,0 +1,36 @@
+"""The draft kernel must not spill vector registers: with spills this compiler version produced
+wrong results from the kernel's MFMA code (seen on the GPU: NaN / wrong y for the spilled
+instantiations, exact results once the in-flight windows were sized so that nothing spills).
+The check compiles the kernel file for gfx950 and reads the spill counts from the assembly's
+kernel descriptors; it needs hipcc but no GPU."""
+import os
+import re
+import subprocess
+import tempfile
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_draft_kernel_instantiations_do_not_spill():
+    from paper_2511_14102_amd import build as B
+    src = os.path.join(B.CSRC, "draft_int4.hip")
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "draft_int4.s")
+        cmd = [B.HIPCC] + B.FLAGS + ["--cuda-device-only", "-S", src, "-o", out]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr[-2000:]
+        text = open(out).read()
+    names = re.findall(r"\.name:\s+(\S*draft_fused_kernel\S*)", text)
+    spills = re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)
+    sgpr_spills = re.findall(r"\.sgpr_spill_count:\s+(\d+)", text)
+    assert len(names) >= 12                          # 4 token capacities x 3 group sizes
+    blocks = text.split(".name:")
+    checked = 0
+    for blk in blocks[1:]:
+        if "draft_fused_kernel" not in blk.split("\n", 1)[0]:
+            continue
+        m = re.search(r"\.vgpr_spill_count:\s+(\d+)", blk)
+        assert m is not None
+        assert int(m.group(1)) == 0, blk.split("\n", 1)[0].strip()
+        checked += 1
+    assert checked >= 12

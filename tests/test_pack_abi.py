@@ -43,11 +43,10 @@ def test_bf16_tile16x32_layout_matches_the_header_formula():
             assert int(img[o]) | (int(img[o + 1]) << 8) == int(bits[r, c])
 
 
-def _code_at(words, unit_index, lane, c):
-    """Code c (0..31) of the 16-byte unit owned by `lane` of tile `unit_index`."""
-    d, n = c // 8, c % 8
+def _code_at(words, tile, chunk, r, d, n):
+    """Code n (0..7) of the word that lane chunk * 16 + r of `tile` holds for row block d."""
     p = n // 2 if n % 2 == 0 else 4 + n // 2
-    return (int(words[(unit_index * 64 + lane) * 4 + d]) >> (4 * p)) & 15
+    return (int(words[(tile * 64 + chunk * 16 + r) * 4 + d]) >> (4 * p)) & 15
 
 
 def test_int4_slice_layout_matches_the_header_formula():
@@ -61,37 +60,42 @@ def test_int4_slice_layout_matches_the_header_formula():
     assert qb.numel() == 3 * H * I // 2 and sb.numel() == 3 * H * I // g * 4
     words = qb.numpy().view("<u4")
     n_gu_tiles = (I // 32) * (H // 32)
-    for r in range(I):
-        for c in range(H):
-            sl, u = r // 32, c // 32
+    for row in range(I):
+        for col in range(H):
+            sl, u = row // 32, col // 32
             tile = sl * (H // 32) + u
-            assert _code_at(words, tile, r % 32, c % 32) == int(q["gate"][r, c])
-            assert _code_at(words, tile, 32 + r % 32, c % 32) == int(q["up"][r, c])
-    for r in range(H):
-        for c in range(I):
-            tile = n_gu_tiles + (c // 32) * (H // 64) + r // 64
-            assert _code_at(words, tile, r % 64, c % 32) == int(q["down"][r, c])
+            d, r = (row % 32) // 16, row % 16
+            chunk, n = (col % 32) // 8, col % 8
+            assert _code_at(words, tile, chunk, r, d, n) == int(q["gate"][row, col])
+            assert _code_at(words, tile, chunk, r, d + 2, n) == int(q["up"][row, col])
+    for row in range(H):
+        for col in range(I):
+            tile = n_gu_tiles + (col // 32) * (H // 64) + row // 64
+            d, r = (row % 64) // 16, row % 16
+            assert _code_at(words, tile, (col % 32) // 8, r, d, col % 8) == int(q["down"][row, col])
     ent = sb.numpy().view("<u2").reshape(-1, 2)
     G = H // g
     bits = lambda t: t.numpy().view(np.uint16)
-    for r in range(I):
+    for row in range(I):
         for gi in range(G):
-            i = ((r // 32) * G + gi) * 64 + r % 32
-            assert ent[i, 0] == bits(s["gate"])[r, gi] and ent[i, 1] == bits(z["gate"])[r, gi]
-            assert ent[i + 32, 0] == bits(s["up"])[r, gi] and ent[i + 32, 1] == bits(z["up"])[r, gi]
+            d, r = (row % 32) // 16, row % 16
+            i = (((row // 32) * G + gi) * 16 + r) * 4 + d
+            assert ent[i, 0] == bits(s["gate"])[row, gi] and ent[i, 1] == bits(z["gate"])[row, gi]
+            assert ent[i + 2, 0] == bits(s["up"])[row, gi] and ent[i + 2, 1] == bits(z["up"])[row, gi]
     base = (I // 32) * G * 64
-    for r in range(H):
+    for row in range(H):
         for gi in range(I // g):
-            i = base + gi * H + r
-            assert ent[i, 0] == bits(s["down"])[r, gi] and ent[i, 1] == bits(z["down"])[r, gi]
+            d, r = (row % 64) // 16, row % 16
+            i = base + ((gi * (H // 64) + row // 64) * 16 + r) * 4 + d
+            assert ent[i, 0] == bits(s["down"])[row, gi] and ent[i, 1] == bits(z["down"])[row, gi]
 
 
 def test_code_pairs_unpack_with_one_mask():
     # the property the kernel relies on: ((word >> 4j) & 0x000F000F) holds codes (2j, 2j+1)
     q = torch.zeros((64, 32), dtype=torch.uint8)
     q[5, 8:16] = torch.tensor([3, 14, 1, 7, 9, 0, 15, 6], dtype=torch.uint8)
-    words = pack.pack_int4_down_codes(q).numpy().view("<u4").reshape(64, 4)
-    w = int(words[5, 1])
+    words = pack.pack_int4_down_codes(q).numpy().view("<u4").reshape(64, 4)   # [lane, d]
+    w = int(words[1 * 16 + 5, 0])                                             # chunk 1, r 5, row block 0
     got = []
     for j in range(4):
         m = (w >> (4 * j)) & 0x000F000F
