@@ -40,6 +40,7 @@
 //      the tags and the ticket counters at its end, so the workspace is back in its idle state
 //      when the kernel ends.  This also holds when the same launch is replayed from a HIP graph.
 #include "plan.h"
+#include "wave.h"
 
 namespace moespeq {
 
@@ -103,22 +104,6 @@ __device__ inline u32x4 load16_agent(const void *p) {
 
 __device__ inline void store16_agent(void *p, u32x4 v) {
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
-}
-
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-__device__ inline double wave_sum_f64(double v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-__device__ inline double wave_max_f64(double v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmax(v, __shfl_xor(v, m, 64));
-    return v;
 }
 
 struct FusedArgs {
@@ -196,7 +181,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     acc += (double)(bf16_hi(xs[i]) * bf16_hi(ws[i]));
                 }
             }
-            acc = wave_sum_f64(acc);
+            acc = wave::sum(acc);
             if (lane == 0) s_part[wave] = acc;
             __syncthreads();                                             // also: every thread's clearing is done
             if (tid < kReplicas) {                                       // thread r writes replica r
@@ -229,7 +214,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         const uint16_t *src = s_x + t * xstride + gi * g + part * per;
         float v = 0.f;
         for (int j = 0; j < per; ++j) v += __uint_as_float((uint32_t)src[j] << 16);
-        v += __shfl_xor(v, 1, 64); v += __shfl_xor(v, 2, 64); v += __shfl_xor(v, 4, 64); v += __shfl_xor(v, 8, 64);
+        v = wave::row_sum(v);
         if (part == 0) s_xsum[t * G + gi] = v;
     }
 
@@ -261,31 +246,26 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         double mx = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
-        mx = wave_max_f64(mx);
+        mx = wave::max(mx);
         // the selection compares the fp64 logits; the softmax values only have to be good to
         // fp32, so they are computed in fp32 from the fp64 differences
         float den = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if (lane + 64 * i < E) den += expf((float)(l[i] - mx));
-        den = wave_sum(den);
+        den = wave::sum(den);
         unsigned taken = 0;
         float sel_sum = 0.f, my_conf = 0.f;
         int my_id = 0;
         for (int j = 0; j < k; ++j) {
             double bv = -INFINITY;
-            int bi = 0x7fffffff;
+            int bi = wave::kNone;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int e = lane + 64 * i;
-                if (e < E && !((taken >> i) & 1) && (bi == 0x7fffffff || l[i] > bv)) { bv = l[i]; bi = e; }
+                if (e < E && !((taken >> i) & 1) && (bi == wave::kNone || l[i] > bv)) { bv = l[i]; bi = e; }
             }
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) {
-                const double ov = __shfl_xor(bv, m, 64);
-                const int oi = __shfl_xor(bi, m, 64);
-                if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
-            }
+            { const wave::Best b = wave::argmax(wave::Best{bv, bi}); bv = b.v; bi = b.i; }
             if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
             const float p = expf((float)(bv - mx)) / den;
             sel_sum += p;
@@ -328,6 +308,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
     if (tid == 0) s_cnt = 0;
+    if (tid < MT) s_hsum[tid] = 0.f;
     __syncthreads();
     if (expert >= 0 && wave == 0) {             // rows of the item: assignments with this expert, ascending
         int cnt = 0;
@@ -469,14 +450,13 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 const uint16_t lo = f32_to_bf16_rne(h - __uint_as_float((uint32_t)hi << 16));
                 s_hhi[slot][d * 16 + (lr & 15)] = hi;
                 s_hlo[slot][d * 16 + (lr & 15)] = lo;
+                // sum of the represented h over the slice, per token: the 16 lanes of a
+                // (slot, row block) group add up in a fixed order, and the slot's two group
+                // sums meet in LDS (two addends commute, so the result does not depend on order)
+                float hs = __uint_as_float((uint32_t)hi << 16) + __uint_as_float((uint32_t)lo << 16);
+                hs = wave::row_sum(hs);
+                if ((lr & 15) == 0) atomicAdd(&s_hsum[slot], hs);
             }
-        }
-        __syncthreads();
-        if (tid < cnt) {                         // sum of the represented h over the slice, per token
-            float hs = 0.f;
-            for (int j = 0; j < 32; ++j)
-                hs += __uint_as_float((uint32_t)s_hhi[tid][j] << 16) + __uint_as_float((uint32_t)s_hlo[tid][j] << 16);
-            s_hsum[tid] = hs;
         }
         __syncthreads();
 

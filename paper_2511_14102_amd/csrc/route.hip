@@ -9,6 +9,7 @@
 // Section 3.4.4: assignments are regrouped per expert.  Section 2.3 / 3.2.2: union of the
 // experts of a window and the part of it that is not resident.
 #include "plan.h"
+#include "wave.h"
 
 namespace moespeq {
 
@@ -18,18 +19,6 @@ constexpr int kRouteThreads = 1024;
 
 __device__ inline double bf16_to_f64(uint16_t b) {
     return (double)__uint_as_float((uint32_t)b << 16);
-}
-
-__device__ inline double wave_sum_f64(double v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-
-__device__ inline double wave_max_f64(double v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmax(v, __shfl_xor(v, m, 64));
-    return v;
 }
 
 // One workgroup per token: logits of all experts (one wave per expert row at a time), then
@@ -60,7 +49,7 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
                 acc = fma(bf16_to_f64((uint16_t)(xs[i] >> 16)), bf16_to_f64((uint16_t)(ws[i] >> 16)), acc);
             }
         }
-        acc = wave_sum_f64(acc);
+        acc = wave::sum(acc);
         if (lane == 0) s_logit[e] = acc + (bias ? (double)bias[e] : 0.0);
     }
 
@@ -75,12 +64,12 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
         l[i] = e < E ? s_logit[e] : -INFINITY;
         mx = fmax(mx, l[i]);
     }
-    mx = wave_max_f64(mx);
+    mx = wave::max(mx);
     double den = 0.0;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         if (lane + 64 * i < E) den += exp(l[i] - mx);
-    den = wave_sum_f64(den);
+    den = wave::sum(den);
 
     unsigned taken = 0;
     double sel_sum = 0.0;
@@ -88,18 +77,13 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
     int my_id = 0;
     for (int j = 0; j < k; ++j) {
         double bv = -INFINITY;
-        int bi = 0x7fffffff;
+        int bi = wave::kNone;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int e = lane + 64 * i;
-            if (e < E && !((taken >> i) & 1) && (bi == 0x7fffffff || l[i] > bv)) { bv = l[i]; bi = e; }
+            if (e < E && !((taken >> i) & 1) && (bi == wave::kNone || l[i] > bv)) { bv = l[i]; bi = e; }
         }
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            double ov = __shfl_xor(bv, m, 64);
-            int oi = __shfl_xor(bi, m, 64);
-            if (oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi))) { bv = ov; bi = oi; }
-        }
+        { const wave::Best b = wave::argmax(wave::Best{bv, bi}); bv = b.v; bi = b.i; }
         if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
         double p = exp(bv - mx) / den;
         sel_sum += p;

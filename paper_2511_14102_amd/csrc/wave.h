@@ -1,0 +1,87 @@
+// Wave-wide (64 lanes) reductions for gfx950 through the data-parallel-primitive lane moves of
+// the vector ALU instead of LDS-routed lane permutes: a dependent chain of six permutes costs
+// around a thousand cycles, the same chain of DPP moves a few tens.  All results are the same in
+// every lane and do not depend on timing (fixed combination order).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moespeq {
+namespace wave {
+
+// DPP controls: partner lanes inside a row of 16 lanes
+constexpr int kSwap1 = 0xB1;        // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int kSwap2 = 0x4E;        // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int kHalfMirror = 0x141;  // lane i <-> 7 - i inside each 8 lanes (the other quad)
+constexpr int kMirror = 0x140;      // lane i <-> 15 - i inside the row (the other half)
+
+template <int kCtrl>
+__device__ inline uint32_t move(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, 0xF, 0xF, false);
+}
+template <int kCtrl>
+__device__ inline float move(float v) { return __uint_as_float(move<kCtrl>(__float_as_uint(v))); }
+template <int kCtrl>
+__device__ inline int move(int v) { return (int)move<kCtrl>((uint32_t)v); }
+template <int kCtrl>
+__device__ inline double move(double v) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = move<kCtrl>((uint32_t)b), hi = move<kCtrl>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// value of lane `kLane`, as a wave-uniform value
+template <int kLane>
+__device__ inline uint32_t from_lane(uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane((int)v, kLane); }
+template <int kLane>
+__device__ inline float from_lane(float v) { return __uint_as_float(from_lane<kLane>(__float_as_uint(v))); }
+template <int kLane>
+__device__ inline int from_lane(int v) { return __builtin_amdgcn_readlane(v, kLane); }
+template <int kLane>
+__device__ inline double from_lane(double v) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = from_lane<kLane>((uint32_t)b), hi = from_lane<kLane>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// Largest value over the wave with its index; among equal values the lower index wins.  A lane
+// with nothing to offer passes index kNone.  (value, index) pairs are ordered strictly, so both
+// partners of a step keep the same pair.
+constexpr int kNone = 0x7fffffff;
+struct Best { double v; int i; };
+__device__ inline Best better(Best a, Best b) {
+    const bool take = b.i != kNone && (a.i == kNone || b.v > a.v || (b.v == a.v && b.i < a.i));
+    return take ? b : a;
+}
+template <int kCtrl>
+__device__ inline Best move(Best b) { return Best{move<kCtrl>(b.v), move<kCtrl>(b.i)}; }
+template <int kLane>
+__device__ inline Best from_lane(Best b) { return Best{from_lane<kLane>(b.v), from_lane<kLane>(b.i)}; }
+// Reduction over each row of 16 lanes with a commutative `op`; every lane of the row gets the
+// row's result.  After the two quad steps a quad's lanes agree, so the mirror moves pair
+// disjoint, already reduced groups.
+template <typename T, typename Op>
+__device__ inline T row_all(T v, Op op) {
+    v = op(v, move<kSwap1>(v));
+    v = op(v, move<kSwap2>(v));
+    v = op(v, move<kHalfMirror>(v));
+    v = op(v, move<kMirror>(v));
+    return v;
+}
+
+// Reduction over the wave: rows first, then the four row results in row order.
+template <typename T, typename Op>
+__device__ inline T all(T v, Op op) {
+    v = row_all(v, op);
+    return op(op(op(from_lane<0>(v), from_lane<16>(v)), from_lane<32>(v)), from_lane<48>(v));
+}
+
+__device__ inline float sum(float v) { return all(v, [](float a, float b) { return a + b; }); }
+__device__ inline double sum(double v) { return all(v, [](double a, double b) { return a + b; }); }
+__device__ inline double max(double v) { return all(v, [](double a, double b) { return fmax(a, b); }); }
+__device__ inline float row_sum(float v) { return row_all(v, [](float a, float b) { return a + b; }); }
+
+__device__ inline Best argmax(Best b) { return all(b, [](Best x, Best y) { return better(x, y); }); }
+
+}  // namespace wave
+}  // namespace moespeq
