@@ -272,23 +272,37 @@ int moe_expert_copy_async(moe_ctx *ctx, void *dst_slot_dev, const void *src_pinn
 #define MOE_KERNEL_ROUTE         0   /* router logits + softmax + top-k (+ fp16 copy of x)   */
 #define MOE_KERNEL_PLAN          1   /* histogram / permutation / expert list / missing list */
 #define MOE_KERNEL_DRAFT_FUSED   2   /* router + top-k + int4 SwiGLU experts, one launch     */
-#define MOE_KERNEL_RESERVED      3
+#define MOE_KERNEL_STREAM_READ   3   /* plain streaming read (moe_stream_read_probe)         */
 #define MOE_KERNEL_BF16_GATEUP   4   /* bf16 gate+up small-M contraction, SwiGLU             */
 #define MOE_KERNEL_BF16_DOWN     5   /* bf16 down small-M contraction                        */
 #define MOE_KERNEL_COMBINE       6   /* weighted sum over a token's experts                  */
 #define MOE_KERNEL_UNION         7   /* expert union                                         */
 #define MOE_KERNEL_COUNT         8
 
-/* With profiling enabled, moe_route_topk / moe_draft_layer_int4 / moe_expert_union /
- * moe_verify_layer_bf16 bracket each kernel launch with a pair of HIP events recorded on the
- * call's stream.  Events are created on demand, so this mode allocates and must not be used
- * under stream capture; it exists for benchmarks only.  Disabling discards pending pairs. */
+/* With profiling enabled, every kernel launch of moe_route_topk / moe_draft_layer_int4 /
+ * moe_expert_union / moe_verify_layer_bf16 / moe_stream_read_probe carries a pair of HIP events
+ * that the runtime stamps with the begin and the end of the kernel's execution on the call's
+ * stream (the duration a kernel trace shows).  Events are created on demand, so this mode
+ * allocates and must not be used under stream capture; it exists for benchmarks only.
+ * Disabling discards pending pairs. */
 int moe_profile_enable(moe_ctx *ctx, int enable);
 /* Waits for every recorded pair of `kernel`, returns the summed elapsed time and the number of
  * launches since the last read, and clears them.  total_ms / launches are HOST pointers. */
 int moe_profile_read(moe_ctx *ctx, int kernel, double *total_ms, int64_t *launches);
 /* Static name of a MOE_KERNEL_* id (the kernel's function name), "" if out of range. */
 const char *moe_kernel_name(int kernel);
+
+/*
+ * Practical ceiling for the weight-streaming kernels: reads `bytes` of device memory at src_dev
+ * once and does nothing else, with `workgroups` workgroups of 512 threads, each wave walking its
+ * own contiguous run of 1 KiB tiles with eight 16-byte non-temporal loads in flight per lane (the
+ * access shape of the draft kernel's weight stream).  bytes: multiple of 1024, >= 1024; src_dev
+ * 16-byte aligned; sink_dev: DEVICE pointer to >= 4 writable bytes (written only if the fold of
+ * the data equals one reserved word; never read).  Timed like the other kernels through
+ * moe_profile_read(MOE_KERNEL_STREAM_READ).  MOE_ERR_INVALID_ARG on bad arguments.
+ */
+int moe_stream_read_probe(moe_ctx *ctx, const void *src_dev, size_t bytes, int workgroups,
+                          void *sink_dev, void *stream);
 
 #ifdef __cplusplus
 }

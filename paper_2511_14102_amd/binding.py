@@ -21,7 +21,7 @@ EXPORTS = [
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
     "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
-    "moe_profile_enable", "moe_profile_read", "moe_kernel_name",
+    "moe_profile_enable", "moe_profile_read", "moe_kernel_name", "moe_stream_read_probe",
 ]
 KERNEL_COUNT = 8
 
@@ -82,6 +82,7 @@ def load_library():
         L.moe_profile_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_double),
                                        ctypes.POINTER(ctypes.c_int64)]
         L.moe_kernel_name.argtypes = [i32]; L.moe_kernel_name.restype = ctypes.c_char_p
+        L.moe_stream_read_probe.argtypes = [vp, vp, ctypes.c_size_t, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("moe_status_string", "moe_last_hip_error", "moe_bf16_expert_bytes",
                          "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes", "moe_kernel_name"):
@@ -200,6 +201,10 @@ class Context:
             ev = ctypes.c_void_p(done_event.cuda_event)
         self._check(self._lib.moe_expert_copy_async(self._h, _ptr(dst_slot), _ptr(src_pinned), nbytes,
                                                     _stream(copy_stream), ev), "moe_expert_copy_async")
+
+    def stream_read_probe(self, src, nbytes, workgroups, sink, stream=None):
+        self._check(self._lib.moe_stream_read_probe(self._h, _ptr(src), nbytes, workgroups, _ptr(sink),
+                                                    _stream(stream)), "moe_stream_read_probe")
 
     def profile_enable(self, enable: bool):
         self._check(self._lib.moe_profile_enable(self._h, int(bool(enable))), "moe_profile_enable")

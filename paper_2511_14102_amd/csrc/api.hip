@@ -78,24 +78,33 @@ static int hip_status(moe_ctx *ctx, hipError_t e)
     return MOE_ERR_HIP;
 }
 
-// Brackets one kernel launch with an event pair when profiling is on.
+thread_local LaunchTiming g_launch_timing = {nullptr, nullptr};
+
+// With profiling on, hands the next kernel launch of this thread an event pair that the runtime
+// stamps with the kernel's begin and end.  One launch per scope.
 struct ProfScope {
-    moe_ctx *ctx; int kernel; hipStream_t st; hipEvent_t stop;
     static hipEvent_t take(moe_ctx *c) {
         hipEvent_t e = nullptr;
         if (!c->free_events.empty()) { e = c->free_events.back(); c->free_events.pop_back(); }
         else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
         return e;
     }
-    ProfScope(moe_ctx *c, int k, hipStream_t s) : ctx(c), kernel(k), st(s), stop(nullptr) {
+    moe_ctx *ctx; int kernel;
+    ProfScope(moe_ctx *c, int k, hipStream_t) : ctx(c), kernel(k) {
         if (!ctx->profiling) return;
-        hipEvent_t start = take(ctx);
-        stop = take(ctx);
-        if (!start || !stop) { stop = nullptr; return; }
-        (void)hipEventRecord(start, st);
+        hipEvent_t start = take(ctx), stop = take(ctx);
+        if (!start || !stop) return;
+        g_launch_timing = LaunchTiming{start, stop};
         ctx->pairs[kernel].push_back(std::make_pair(start, stop));
     }
-    ~ProfScope() { if (stop) (void)hipEventRecord(stop, st); }
+    ~ProfScope() {
+        if (g_launch_timing.stop) {          // nothing was launched inside the scope
+            ctx->free_events.push_back(g_launch_timing.start);
+            ctx->free_events.push_back(g_launch_timing.stop);
+            ctx->pairs[kernel].pop_back();
+            g_launch_timing = LaunchTiming{nullptr, nullptr};
+        }
+    }
 };
 
 }  // namespace moespeq
@@ -176,7 +185,7 @@ int moe_profile_read(moe_ctx *ctx, int kernel, double *total_ms, int64_t *launch
 const char *moe_kernel_name(int kernel)
 {
     static const char *names[MOE_KERNEL_COUNT] = {
-        "route_kernel", "plan_kernel", "draft_fused_kernel", "(unused)",
+        "route_kernel", "plan_kernel", "draft_fused_kernel", "stream_read_kernel",
         "bf16_gateup_kernel", "bf16_down_kernel", "combine_kernel", "union_kernel"};
     return (kernel >= 0 && kernel < MOE_KERNEL_COUNT) ? names[kernel] : "";
 }
@@ -377,6 +386,17 @@ int moe_expert_copy_async(moe_ctx *ctx, void *dst, const void *src, size_t bytes
     hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, (hipStream_t)copy_stream);
     if (e == hipSuccess && done_event) e = hipEventRecord((hipEvent_t)done_event, (hipStream_t)copy_stream);
     return hip_status(ctx, e);
+}
+
+int moe_stream_read_probe(moe_ctx *ctx, const void *src, size_t bytes, int workgroups, void *sink,
+                          void *stream)
+{
+    if (!ctx || !src || !sink || bytes < 1024 || bytes % 1024 || ((uintptr_t)src & 15) ||
+        ((uintptr_t)sink & 3) || workgroups < 1 || workgroups > 65536)
+        return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    { ProfScope p(ctx, MOE_KERNEL_STREAM_READ, st); launch_stream_read(src, bytes, workgroups, sink, st); }
+    return hip_status(ctx, hipGetLastError());
 }
 
 }  // extern "C"

@@ -241,10 +241,10 @@ void launch_bf16_gateup(const Shape &s, const Plan *plan, int first_active, int 
     if (n_active_max <= 0) return;
     const dim3 grid(s.I / 16, n_active_max), block(kWaves * 64);
     if (hb_lo)
-        hipLaunchKernelGGL(bf16_gateup_kernel<true>, grid, block, 0, st, plan, first_active,
+        launch(bf16_gateup_kernel<true>, grid, block, 0, st, plan, first_active,
                            (const uint16_t *)x, (uint16_t *)hb, (uint16_t *)hb_lo, s.H, s.I);
     else
-        hipLaunchKernelGGL(bf16_gateup_kernel<false>, grid, block, 0, st, plan, first_active,
+        launch(bf16_gateup_kernel<false>, grid, block, 0, st, plan, first_active,
                            (const uint16_t *)x, (uint16_t *)hb, (uint16_t *)nullptr, s.H, s.I);
 }
 
@@ -254,10 +254,10 @@ void launch_bf16_down(const Shape &s, const Plan *plan, int first_active, int n_
     if (n_active_max <= 0) return;
     const dim3 grid(s.H / 16, n_active_max), block(kWaves * 64);
     if (hb_lo)
-        hipLaunchKernelGGL(bf16_down_kernel<true>, grid, block, 0, st, plan, first_active,
+        launch(bf16_down_kernel<true>, grid, block, 0, st, plan, first_active,
                            (const uint16_t *)hb, (const uint16_t *)hb_lo, obuf, s.H, s.I);
     else
-        hipLaunchKernelGGL(bf16_down_kernel<false>, grid, block, 0, st, plan, first_active,
+        launch(bf16_down_kernel<false>, grid, block, 0, st, plan, first_active,
                            (const uint16_t *)hb, (const uint16_t *)nullptr, obuf, s.H, s.I);
 }
 
@@ -266,10 +266,10 @@ void launch_combine(const Shape &s, const Plan *plan, const float *routed, int n
 {
     dim3 grid((s.H + 1023) / 1024, s.T);
     if (out_bf16)
-        hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(256), 0, st, plan, routed, nsplit, obuf,
+        launch(combine_kernel<true>, grid, dim3(256), 0, st, plan, routed, nsplit, obuf,
                            accumulate, y, s.T, s.H, s.k, s.S);
     else
-        hipLaunchKernelGGL(combine_kernel<false>, grid, dim3(256), 0, st, plan, routed, nsplit, obuf,
+        launch(combine_kernel<false>, grid, dim3(256), 0, st, plan, routed, nsplit, obuf,
                            accumulate, y, s.T, s.H, s.k, s.S);
 }
 

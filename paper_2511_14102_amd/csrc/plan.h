@@ -2,10 +2,30 @@
 // and that the expert kernels read, plus the host-side launcher prototypes of each .hip file.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include "../../include/moespeq.h"
 
 namespace moespeq {
+
+// Every kernel of the library is launched through launch().  When a timing pair is pending on
+// this host thread (set by the profiling mode of the C ABI) the launch carries it: the runtime
+// then stamps `start` / `stop` with the begin and end of the kernel's own execution, which is the
+// duration a kernel trace reports, without the gaps an event recorded before and after would add.
+struct LaunchTiming { hipEvent_t start, stop; };
+extern thread_local LaunchTiming g_launch_timing;
+
+template <typename K, typename... A>
+inline void launch(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, A... args)
+{
+    if (g_launch_timing.stop) {
+        const LaunchTiming t = g_launch_timing;
+        g_launch_timing = LaunchTiming{nullptr, nullptr};
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, t.start, t.stop, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+    }
+}
 
 constexpr int kMaxRows = MOE_MAX_ASSIGN + MOE_MAX_TOKENS * MOE_MAX_SHARED;   // routed + shared rows
 constexpr int kMaxActive = MOE_MAX_ASSIGN + MOE_MAX_SHARED;                   // distinct experts per call
@@ -82,6 +102,7 @@ struct DraftFusedArgs {
 };
 void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
 void launch_zero(void *p, size_t bytes, hipStream_t st);
+void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st);
 
 // expert_bf16.hip
 // hb_lo != nullptr: the intermediate is kept as a bf16 hi + lo pair (draft-pass precision)

@@ -267,7 +267,7 @@ void union_kernel(const int32_t *__restrict__ ids, int n_ids, int E,
 void launch_route(const Shape &s, const void *x, const void *wr, const float *bias,
                   int32_t *ids, float *w, float *conf, hipStream_t st)
 {
-    hipLaunchKernelGGL(route_kernel, dim3(s.T), dim3(kRouteThreads), 0, st,
+    launch(route_kernel, dim3(s.T), dim3(kRouteThreads), 0, st,
                        (const uint16_t *)x, (const uint16_t *)wr, bias, s.H, s.E, s.k, s.renorm,
                        ids, w, conf);
 }
@@ -275,12 +275,12 @@ void launch_route(const Shape &s, const void *x, const void *wr, const float *bi
 void launch_perm(const Shape &s, const int32_t *ids, int32_t *count, int32_t *off,
                  int32_t *perm, hipStream_t st)
 {
-    hipLaunchKernelGGL(perm_kernel, dim3(1), dim3(256), 0, st, ids, s.T * s.k, s.E, count, off, perm);
+    launch(perm_kernel, dim3(1), dim3(256), 0, st, ids, s.T * s.k, s.E, count, off, perm);
 }
 
 void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st)
 {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, a.plan, s.T, s.E, s.k, s.S, a.mode,
+    launch(plan_kernel, dim3(1), dim3(256), 0, st, a.plan, s.T, s.E, s.k, s.S, a.mode,
                        (const char *)a.w0, a.stride0, (const char *)a.w1, a.stride1,
                        a.slot_of_expert, (const char *)a.shared, a.shared_stride, a.flags,
                        a.ids_out, a.conf_out, a.missing, a.n_missing);
@@ -290,7 +290,7 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
                   uint64_t *mask, int32_t *list, int32_t *n_list,
                   int32_t *missing, int32_t *n_missing, hipStream_t st)
 {
-    hipLaunchKernelGGL(union_kernel, dim3(1), dim3(256), 0, st, ids, n_ids, E, slot, mask, list,
+    launch(union_kernel, dim3(1), dim3(256), 0, st, ids, n_ids, E, slot, mask, list,
                        n_list, missing, n_missing);
 }
 
