@@ -164,7 +164,9 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         const int nprod = E < (int)gridDim.x ? E : (int)gridDim.x;
         for (int i = blockIdx.x * kThreads + tid; i < T * H; i += nprod * kThreads)
             __hip_atomic_store(&a.y[i], 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // the clearing stores have completed
+        // the clearing stores have been performed before this workgroup publishes anything (a
+        // workgroup-scope release fence does not imply the wait)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     for (int e = blockIdx.x; e < E; e += gridDim.x) {
         const uint16_t *row = a.wr + (size_t)e * H;
@@ -461,12 +463,23 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         __syncthreads();
 
         // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns
-        const int hslot = r < cnt ? r : 0;
-        const u32x4 ha_hi = *reinterpret_cast<const u32x4 *>(&s_hhi[hslot][c * 8]);
-        const u32x4 ha_lo = *reinterpret_cast<const u32x4 *>(&s_hlo[hslot][c * 8]);
-        float hsum[NI];
+        // A rows 2t and 2t + 1 are the hi and the lo part of token slot t, so one MFMA yields
+        // both products and a token's output is the sum of two D registers of one lane: lane
+        // group c holds token slots 2c and 2c + 1
+        constexpr int ND = MT < 2 ? 1 : 2;           // token slots per lane
+        constexpr int NCD = (MT + 1) / 2;            // lane groups with valid slots
+        const int hslot = (r >> 1) < cnt ? (r >> 1) : 0;
+        const u32x4 ha = *reinterpret_cast<const u32x4 *>((r & 1) ? &s_hlo[hslot][c * 8] : &s_hhi[hslot][c * 8]);
+        float hsum[ND], rwd[ND];
+        int tokd[ND];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) hsum[i] = s_hsum[4 * c + i < cnt ? 4 * c + i : 0];
+        for (int i = 0; i < ND; ++i) {
+            const int slot = 2 * c + i < cnt ? 2 * c + i : 0;
+            const int arow = s_row_a[slot];
+            hsum[i] = s_hsum[slot];
+            tokd[i] = arow / k;
+            rwd[i] = s_w[arow];
+        }
         for (int j0 = 0; wave + j0 * kWaves < nrt; j0 += kDownWin) {
 #pragma unroll
             for (int i = 0; i < kDownWin; ++i) {
@@ -482,16 +495,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
                         const bf16x8 b = unpack8(qw[d], uk);
-                        f32x4 o = mfma(ha_hi, b, (f32x4){0.f, 0.f, 0.f, 0.f});
-                        o = mfma(ha_lo, b, o);
+                        const f32x4 o = mfma(ha, b, (f32x4){0.f, 0.f, 0.f, 0.f});
                         const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] & 0xffff));
                         const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] >> 16)) + 128.f;
-                        if (c < NC) {
+                        if (c < NCD) {
 #pragma unroll
-                            for (int j = 0; j < NI; ++j) {
-                                if (4 * c + j < cnt) {
-                                    const float val = sc * (o[j] - zp * hsum[j]) * rw[j];
-                                    __hip_atomic_fetch_add(&a.y[(size_t)tok[j] * H + rt * 64 + d * 16 + r], val,
+                            for (int j = 0; j < ND; ++j) {
+                                if (2 * c + j < cnt) {
+                                    const float val = sc * ((o[2 * j] + o[2 * j + 1]) - zp * hsum[j]) * rwd[j];
+                                    __hip_atomic_fetch_add(&a.y[(size_t)tokd[j] * H + rt * 64 + d * 16 + r], val,
                                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                                 }
                             }
