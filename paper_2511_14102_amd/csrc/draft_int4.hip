@@ -164,9 +164,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         const int nprod = E < (int)gridDim.x ? E : (int)gridDim.x;
         for (int i = blockIdx.x * kThreads + tid; i < T * H; i += nprod * kThreads)
             __hip_atomic_store(&a.y[i], 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // the clearing stores have been performed before this workgroup publishes anything (a
-        // workgroup-scope release fence does not imply the wait)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     for (int e = blockIdx.x; e < E; e += gridDim.x) {
         const uint16_t *row = a.wr + (size_t)e * H;
@@ -185,7 +182,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
             acc = wave::sum(acc);
             if (lane == 0) s_part[wave] = acc;
-            __syncthreads();                                             // also: every thread's clearing is done
+            // every thread's clearing stores have been performed before the workgroup publishes (a
+            // workgroup-scope release fence does not imply this wait; it is free here, the loads
+            // of the row were issued after the stores and have returned)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
             if (tid < kReplicas) {                                       // thread r writes replica r
                 double l = 0.0;
                 for (int w = 0; w < kWaves; ++w) l += s_part[w];
