@@ -23,6 +23,11 @@ EXPORTS = [
     "moe_verify_layer_bf16", "moe_expert_copy_async",
     "moe_profile_enable", "moe_profile_read", "moe_kernel_name", "moe_stream_read_probe",
 ]
+# include/moespeq_sched.h (host-side control plane)
+SCHED_EXPORTS = [
+    "moe_governor_create", "moe_governor_destroy", "moe_governor_observe", "moe_governor_probabilities",
+    "moe_governor_k_accept", "moe_governor_cycle_time", "moe_governor_evaluate", "moe_governor_choose_k",
+]
 KERNEL_COUNT = 8
 
 

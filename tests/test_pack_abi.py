@@ -16,16 +16,23 @@ from paper_2511_14102_amd import pack
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "moespeq.h")).read()
+def _declared(header):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", hdr))
+    return set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", hdr))
+
+
+def test_library_exports_every_declared_symbol():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["moespeq.h", "moespeq_sched.h"]
+    names = _declared("moespeq.h")
     assert {"moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
             "moe_verify_layer_bf16", "moe_expert_copy_async"} <= names
+    sched = _declared("moespeq_sched.h")
     lib = ctypes.CDLL(B.library_path())
-    for n in sorted(names):
+    for n in sorted(names | sched):
         assert hasattr(lib, n), n
     assert names == set(B.EXPORTS)
+    assert sched == set(B.SCHED_EXPORTS)
 
 
 def test_bf16_tile16x32_layout_matches_the_header_formula():
