@@ -27,6 +27,9 @@ EXPORTS = [
 SCHED_EXPORTS = [
     "moe_governor_create", "moe_governor_destroy", "moe_governor_observe", "moe_governor_probabilities",
     "moe_governor_k_accept", "moe_governor_cycle_time", "moe_governor_evaluate", "moe_governor_choose_k",
+    "moe_elb_create", "moe_elb_destroy", "moe_elb_reset", "moe_elb_put_step", "moe_elb_steps", "moe_elb_entry",
+    "moe_cache_create", "moe_cache_destroy", "moe_cache_place", "moe_cache_slot_table", "moe_cache_use",
+    "moe_cache_stats", "moe_cache_end_window", "moe_sched_plan", "moe_sched_on_demand",
 ]
 KERNEL_COUNT = 8
 

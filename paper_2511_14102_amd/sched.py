@@ -101,3 +101,148 @@ class Governor:
         _check(self._L.moe_governor_choose_k(self._h, arr, k_slo, ctypes.byref(k), ctypes.byref(th)),
                "moe_governor_choose_k")
         return k.value, th.value
+
+
+# ---- Expert Lookahead Buffer and expert cache --------------------------------------------------
+PHASE_PRIME, PHASE_GUIDED, PHASE_SATURATE = 1, 2, 3
+
+
+class Fetch(ctypes.Structure):
+    _fields_ = [("layer", ctypes.c_int32), ("expert", ctypes.c_int32), ("slot", ctypes.c_int32),
+                ("evicted", ctypes.c_int32)]
+
+    def astuple(self):
+        return (self.layer, self.expert, self.slot, self.evicted)
+
+
+_ready2 = False
+
+
+def _lib2():
+    global _ready2
+    L = _lib()
+    if not _ready2:
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        ip, fp = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float)
+        L.moe_elb_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32]
+        L.moe_elb_destroy.argtypes = [vp]
+        L.moe_elb_reset.argtypes = [vp]
+        L.moe_elb_put_step.argtypes = [vp, i32, ip, fp]
+        L.moe_elb_steps.argtypes = [vp, ip]
+        L.moe_elb_entry.argtypes = [vp, i32, i32, ip, fp]
+        L.moe_cache_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32]
+        L.moe_cache_destroy.argtypes = [vp]
+        L.moe_cache_place.argtypes = [vp, i32, i32, i32]
+        L.moe_cache_slot_table.argtypes = [vp, i32, ip]
+        L.moe_cache_use.argtypes = [vp, i32, ip, i32, ip, ip]
+        L.moe_cache_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]
+        L.moe_cache_end_window.argtypes = [vp]
+        L.moe_sched_plan.argtypes = [vp, vp, i32, i32, ctypes.c_float, ctypes.POINTER(Fetch), i32, ip]
+        L.moe_sched_on_demand.argtypes = [vp, i32, ip, i32, ctypes.POINTER(Fetch)]
+        for n in B.SCHED_EXPORTS:
+            getattr(L, n).restype = i32
+        _ready2 = True
+    return L
+
+
+def _ints(seq):
+    seq = [int(v) for v in seq]
+    return (ctypes.c_int32 * max(len(seq), 1))(*seq), len(seq)
+
+
+class Elb:
+    def __init__(self, n_layers: int, k_max: int, top_k: int):
+        self._L = _lib2()
+        h = ctypes.c_void_p()
+        _check(self._L.moe_elb_create(ctypes.byref(h), n_layers, k_max, top_k), "moe_elb_create")
+        self._h, self.n_layers, self.top_k = h, n_layers, top_k
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.moe_elb_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self):
+        _check(self._L.moe_elb_reset(self._h), "moe_elb_reset")
+
+    def put_step(self, step: int, ids, conf=None):
+        """ids / conf: [n_layers][top_k] nested sequences (or flat)."""
+        flat = [int(v) for row in ids for v in (row if hasattr(row, "__len__") else [row])]
+        arr, _ = _ints(flat)
+        cf = None
+        if conf is not None:
+            cflat = [float(v) for row in conf for v in (row if hasattr(row, "__len__") else [row])]
+            cf = (ctypes.c_float * len(cflat))(*cflat)
+        _check(self._L.moe_elb_put_step(self._h, step, arr, cf), "moe_elb_put_step")
+
+    def steps(self) -> int:
+        n = ctypes.c_int32()
+        _check(self._L.moe_elb_steps(self._h, ctypes.byref(n)), "moe_elb_steps")
+        return n.value
+
+    def entry(self, step: int, layer: int):
+        ids = (ctypes.c_int32 * self.top_k)()
+        cf = (ctypes.c_float * self.top_k)()
+        _check(self._L.moe_elb_entry(self._h, step, layer, ids, cf), "moe_elb_entry")
+        return list(ids), list(cf)
+
+
+class Cache:
+    def __init__(self, n_layers: int, n_experts: int, n_slots: int):
+        self._L = _lib2()
+        h = ctypes.c_void_p()
+        _check(self._L.moe_cache_create(ctypes.byref(h), n_layers, n_experts, n_slots), "moe_cache_create")
+        self._h, self.n_layers, self.n_experts, self.n_slots = h, n_layers, n_experts, n_slots
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.moe_cache_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def place(self, layer: int, expert: int, slot: int):
+        _check(self._L.moe_cache_place(self._h, layer, expert, slot), "moe_cache_place")
+
+    def slot_table(self, layer: int):
+        t = (ctypes.c_int32 * self.n_experts)()
+        _check(self._L.moe_cache_slot_table(self._h, layer, t), "moe_cache_slot_table")
+        return list(t)
+
+    def use(self, layer: int, ids):
+        arr, n = _ints(ids)
+        h, m = ctypes.c_int32(), ctypes.c_int32()
+        _check(self._L.moe_cache_use(self._h, layer, arr, n, ctypes.byref(h), ctypes.byref(m)), "moe_cache_use")
+        return h.value, m.value
+
+    def stats(self):
+        h, m = ctypes.c_int64(), ctypes.c_int64()
+        _check(self._L.moe_cache_stats(self._h, ctypes.byref(h), ctypes.byref(m)), "moe_cache_stats")
+        return h.value, m.value
+
+    def end_window(self):
+        _check(self._L.moe_cache_end_window(self._h), "moe_cache_end_window")
+
+    def plan(self, elb: Elb, phase: int, max_fetch: int = 0, min_conf: float = 0.0, max_out: Optional[int] = None):
+        max_out = self.n_layers * self.n_slots if max_out is None else max_out
+        out = (Fetch * max(max_out, 1))()
+        n = ctypes.c_int32()
+        _check(self._L.moe_sched_plan(self._h, elb._h, phase, max_fetch, min_conf, out, max_out, ctypes.byref(n)),
+               "moe_sched_plan")
+        return [out[i].astuple() for i in range(n.value)]
+
+    def on_demand(self, layer: int, missing):
+        arr, n = _ints(missing)
+        out = (Fetch * max(n, 1))()
+        _check(self._L.moe_sched_on_demand(self._h, layer, arr, n, out), "moe_sched_on_demand")
+        return [out[i].astuple() for i in range(n)]
