@@ -262,11 +262,21 @@ def resident_leg(args, cfg, ctx, dev):
 
 # ------------------------------------------------------------------------------------------------
 def offload_leg(args, cfg, ctx, dev):
-    """n_resident of the E experts of every layer start in slots; the rest sit in pinned host memory."""
+    """n_resident of the E experts of every layer start in the expert cache; all experts also sit in
+    pinned host memory.  The Expert Scheduler (moe_elb_*, moe_cache_*, moe_sched_*) decides what
+    to fetch and what to evict; the copies run on a side stream.
+
+    One stack cycle: the K draft tokens go through all layers token by token; after each token its
+    expert ids (one D2H per token) enter the lookahead buffer and a prefetch phase is planned
+    (first token: priming, middle tokens: budgeted prefetch, last token: saturation) whose copies
+    overlap the next token's drafting; then every layer verifies its K+1 rows as soon as its
+    copies are in; experts only the verify call discovers are fetched on demand and added with an
+    ACCUMULATE|ONLY_LISTED call.  Every cycle sees new tokens."""
     import numpy as np
     import torch
     import synth
     from paper_2511_14102_amd import binding as B
+    from paper_2511_14102_amd import sched as S
     from paper_2511_14102_amd.harness import DeviceLayer
 
     T = max(cfg.verify_tokens)
@@ -274,129 +284,143 @@ def offload_leg(args, cfg, ctx, dev):
     n_layers = args.layers or cfg.bench_layers
     H, E, k = cfg.hidden, cfg.n_experts, cfg.top_k
     n_res = cfg.n_resident
-    n_stage = min(E, T * k)                      # staging slots behind the resident ones
+    n_slots = args.slots or (n_res + min(E, T * k))          # default: residents + room for one window's union
     cycles = max(1, args.steps // n_layers)
     warm_cycles = max(1, args.warmup // n_layers)
+    n_tok_sets = warm_cycles + cycles
 
     t0 = time.time()
-    layers, xs, host = [], [], []
+    layers, host = [], []
     L0 = synth.make_layer(cfg, 0, quant_device=dev)
     for li in range(n_layers):
         L = L0 if li == 0 else synth.make_layer(cfg, li, device=dev)
-        D = DeviceLayer(ctx, cfg, L, max_tokens=T, resident=list(range(n_res)), n_slots=n_res + n_stage)
-        hb = torch.empty((E - n_res, D.bf16_bytes), dtype=torch.uint8, pin_memory=True)
-        for e in range(n_res, E):
-            hb[e - n_res].copy_(D._pack_bf16(L, e))
+        D = DeviceLayer(ctx, cfg, L, max_tokens=T, resident=list(range(n_res)), n_slots=n_slots)
+        hb = torch.empty((E, D.bf16_bytes), dtype=torch.uint8, pin_memory=True)
+        for e in range(E):
+            hb[e].copy_(D._pack_bf16(L, e))
         layers.append(D)
         host.append(hb)
-        xs.append(synth.make_tokens(cfg, T, layer=li).to(dev))
         if li:
             del L
         if li % 4 == 0:
-            log("  layer %d/%d on device, %d experts in pinned host memory (%.0f s)" % (li + 1, n_layers, E - n_res, time.time() - t0))
+            log("  layer %d/%d on device, its %d experts in pinned host memory (%.0f s)" % (li + 1, n_layers, E, time.time() - t0))
+    xs = [[synth.make_tokens(cfg, T, layer=li, step=c).to(dev) for li in range(n_layers)] for c in range(n_tok_sets)]
     torch.cuda.synchronize()
     blob = layers[0].bf16_bytes
-    log("setup %.1f s, %.1f GB in HBM, %.1f GB pinned" % (time.time() - t0, torch.cuda.memory_allocated() / 1e9,
-                                                          n_layers * (E - n_res) * blob / 1e9))
+    log("setup %.1f s, %.1f GB in HBM, %.1f GB pinned, %d slots per layer" %
+        (time.time() - t0, torch.cuda.memory_allocated() / 1e9, n_layers * E * blob / 1e9, n_slots))
 
-    yd = torch.empty((n_layers, K, H), dtype=torch.float32, device=dev)
-    win = torch.empty((n_layers, K, k), dtype=torch.int32, device=dev)
-    conf = torch.empty((n_layers, K, k), dtype=torch.float32, device=dev)
+    yd = torch.empty((K, n_layers, H), dtype=torch.float32, device=dev)
+    win = torch.empty((K, n_layers, k), dtype=torch.int32, device=dev)          # [step, layer, k]: one D2H per token
+    wconf = torch.empty((K, n_layers, k), dtype=torch.float32, device=dev)
+    h_win, h_wconf = win.cpu().pin_memory(), wconf.cpu().pin_memory()
     yv = torch.empty((n_layers, T, H), dtype=torch.bfloat16, device=dev)
     idv = torch.empty((n_layers, T, k), dtype=torch.int32, device=dev)
-    mask = torch.empty((E + 63) // 64, dtype=torch.int64, device=dev)
-    lst = torch.empty(E, dtype=torch.int32, device=dev)
-    nl = torch.empty(1, dtype=torch.int32, device=dev)
-    miss1 = torch.zeros((n_layers, E), dtype=torch.int32, device=dev)      # predicted misses (union)
-    nm1 = torch.zeros(n_layers, dtype=torch.int32, device=dev)
-    miss2 = torch.zeros((n_layers, E), dtype=torch.int32, device=dev)      # found by the verify call
-    nm2 = torch.zeros(n_layers, dtype=torch.int32, device=dev)
-    h_miss1, h_nm1 = miss1.cpu().pin_memory(), nm1.cpu().pin_memory()
-    h_miss2, h_nm2 = miss2.cpu().pin_memory(), nm2.cpu().pin_memory()
-    table0 = [D.slot_of_expert.clone() for D in layers]
-    h_table = [D.slot_host.clone().pin_memory() for D in layers]
+    miss = torch.zeros((n_layers, E), dtype=torch.int32, device=dev)
+    nm = torch.zeros(n_layers, dtype=torch.int32, device=dev)
+    h_idv, h_miss, h_nm = idv.cpu().pin_memory(), miss.cpu().pin_memory(), nm.cpu().pin_memory()
+    h_table = [torch.empty(E, dtype=torch.int32).pin_memory() for _ in range(n_layers)]
     for li, D in enumerate(layers):
-        D.missing, D.n_missing = miss2[li], nm2[li:li + 1]
+        D.missing, D.n_missing = miss[li], nm[li:li + 1]
     copy_stream = torch.cuda.Stream()
-    events = [torch.cuda.Event() for _ in range(n_layers)]
+    ready = [torch.cuda.Event() for _ in range(n_layers)]        # the layer's copies and slot table are in
+    drafted = [torch.cuda.Event() for _ in range(K)]
     main = torch.cuda.current_stream()
+    # Phase II budget per drafted token: twice what the link moves while one token drafts (measured
+    # below: about 1.1 ms per token and 55 GB/s, 3.6 experts), so that the copy queue never runs dry
+    state = {"cache": None, "guided_budget": 8}
 
-    def reset_tables():
+    def new_cache():
+        c = S.Cache(n_layers, E, n_slots)
+        for li in range(n_layers):
+            for e in range(n_res):
+                c.place(li, e, e)
+        return c
+
+    def reset_residency():
+        """Back to the initial residents (the slot pools still hold their blobs in slots 0..n_res-1
+        only if nothing overwrote them, so they are copied again)."""
+        state["cache"] = new_cache()
         for li, D in enumerate(layers):
-            D.slot_of_expert.copy_(table0[li])
-            h_table[li].copy_(D.slot_host)
-        torch.cuda.synchronize()
-
-    drafted = [torch.cuda.Event() for _ in range(n_layers)]
-
-    def draft_phase(base=None):
-        """K draft calls + union per layer; the layer's missing list goes to the host right behind
-        it, and (base given) its copies are issued while the next layer's drafts already run."""
-        for li, D in enumerate(layers):
-            x = xs[li]
-            for i in range(K):
-                D.draft(x[i:i + 1], y=yd[li, i:i + 1], ids=win[li, i:i + 1], conf=conf[li, i:i + 1])
-            ctx.expert_union(win[li], K * k, E, D.slot_of_expert, mask, lst, nl, miss1[li], nm1[li:li + 1])
-            h_miss1[li].copy_(miss1[li], non_blocking=True)
-            h_nm1[li:li + 1].copy_(nm1[li:li + 1], non_blocking=True)
-            drafted[li].record(main)
-            if base is not None and li:
-                drafted[li - 1].synchronize()
-                issue_copies(h_miss1, h_nm1, base, wait_main=False, only=li - 1)
-        drafted[n_layers - 1].synchronize()
-        if base is not None:
-            return issue_copies(h_miss1, h_nm1, base, wait_main=False, only=n_layers - 1)
-
-    def issue_copies(h_miss, h_nm, base, wait_main, only=None):
-        """Copies the listed experts of every layer (or of layer `only`) into staging slots
-        base[li]+j; returns bytes."""
-        total = 0
-        if wait_main:
-            copy_stream.wait_stream(main)
-        for li, D in enumerate(layers):
-            if only is not None and li != only:
-                continue
-            n = int(h_nm[li])
-            if n == 0:
-                continue
-            for j in range(n):
-                e = int(h_miss[li, j])
-                slot = n_res + base[li] + j
-                ctx.expert_copy_async(D.slot_view(slot), host[li][e - n_res], blob, copy_stream, None)
-                h_table[li][e] = slot
+            for e in range(n_res):
+                ctx.expert_copy_async(D.slot_view(e), host[li][e], blob, copy_stream, None)
+            h_table[li].copy_(torch.tensor(state["cache"].slot_table(li), dtype=torch.int32))
             with torch.cuda.stream(copy_stream):
                 D.slot_of_expert.copy_(h_table[li], non_blocking=True)
-            events[li].record(copy_stream)
-            base[li] += n
-            total += n * blob
-        return total
-
-    def verify_phase(wait):
-        for li, D in enumerate(layers):
-            if wait and int(h_nm1[li]):
-                main.wait_event(events[li])
-            D.verify(xs[li], y=yv[li], ids=idv[li])
-        h_miss2.copy_(miss2, non_blocking=True)
-        h_nm2.copy_(nm2, non_blocking=True)
-        main.synchronize()
-
-    def demand_phase(base):
-        """Experts the draft window did not predict: fetch, then add their share."""
-        todo = [li for li in range(n_layers) if int(h_nm2[li])]
-        nbytes = issue_copies(h_miss2, h_nm2, base, wait_main=True)
-        for li in todo:
-            main.wait_event(events[li])
-            layers[li].verify(xs[li], flags=B.MOE_VERIFY_ACCUMULATE | B.MOE_VERIFY_ONLY_LISTED, y=yv[li], ids=idv[li])
-        return nbytes, len(todo)
-
-    def cycle():
-        base = [0] * n_layers
-        draft_phase(base)
-        b1 = int(h_nm1.sum()) * blob
-        verify_phase(wait=True)
-        b2, n_demand_layers = demand_phase(base)
         torch.cuda.synchronize()
-        return b1, b2, n_demand_layers
+
+    def issue(fetches, log_list=None):
+        """Copies for a list of (layer, expert, slot, evicted); uploads the touched layers' tables."""
+        touched = []
+        for (li, e, slot, _ev) in fetches:
+            ctx.expert_copy_async(layers[li].slot_view(slot), host[li][e], blob, copy_stream, None)
+            if li not in touched:
+                touched.append(li)
+        for li in touched:
+            h_table[li].copy_(torch.tensor(state["cache"].slot_table(li), dtype=torch.int32))
+            with torch.cuda.stream(copy_stream):
+                layers[li].slot_of_expert.copy_(h_table[li], non_blocking=True)
+            ready[li].record(copy_stream)
+        if log_list is not None:
+            log_list.extend(fetches)
+        return touched
+
+    def plan_step(i, elb, waiting, fetch_log):
+        elb.put_step(i, h_win[i].tolist(), h_wconf[i].tolist())
+        phase = S.PHASE_SATURATE if i == K - 1 else (S.PHASE_PRIME if i == 0 else S.PHASE_GUIDED)
+        fetches = state["cache"].plan(elb, phase, state["guided_budget"], 0.0)
+        for li in issue(fetches, fetch_log):
+            waiting.add(li)
+        return len(fetches)
+
+    def cycle(x, prefetch=True, fetch_log=None):
+        cache = state["cache"]
+        elb = S.Elb(n_layers, K, k)
+        waiting = set()
+        counts = {"predicted": 0, "on_demand": 0}
+        tables0 = [cache.slot_table(li) for li in range(n_layers)]
+        for i in range(K):                                   # draft, token-major
+            for li, D in enumerate(layers):
+                D.draft(x[li][i:i + 1], y=yd[i, li:li + 1], ids=win[i, li:li + 1], conf=wconf[i, li:li + 1])
+            h_win[i].copy_(win[i], non_blocking=True)
+            h_wconf[i].copy_(wconf[i], non_blocking=True)
+            drafted[i].record(main)
+            if prefetch and i:                               # plan token i-1 while token i drafts
+                drafted[i - 1].synchronize()
+                counts["predicted"] += plan_step(i - 1, elb, waiting, fetch_log)
+        drafted[K - 1].synchronize()
+        if prefetch:
+            counts["predicted"] += plan_step(K - 1, elb, waiting, fetch_log)
+        # |E_new(k)| of the governor's model: experts of the first k drafted tokens that the cache
+        # lacked when the cycle began
+        ids_np = h_win.numpy()
+        counts["n_new_by_k"] = [0] + [sum(len({int(e) for e in ids_np[:kk, li].reshape(-1) if tables0[li][int(e)] < 0})
+                                          for li in range(n_layers)) for kk in range(1, K + 1)]
+        for li, D in enumerate(layers):                      # verify, each layer as soon as its experts are in
+            if li in waiting:
+                main.wait_event(ready[li])
+            D.verify(x[li], y=yv[li], ids=idv[li])
+        h_idv.copy_(idv, non_blocking=True)
+        h_miss.copy_(miss, non_blocking=True)
+        h_nm.copy_(nm, non_blocking=True)
+        main.synchronize()
+        copy_stream.wait_stream(main)
+        todo = []
+        for li in range(n_layers):                           # coverage accounting and on-demand fetches
+            cache.use(li, h_idv[li].reshape(-1).tolist())
+            n = int(h_nm[li])
+            if n:
+                fetches = cache.on_demand(li, h_miss[li, :n].tolist())
+                issue(fetches, fetch_log)
+                counts["on_demand"] += n
+                todo.append(li)
+        for li in todo:
+            main.wait_event(ready[li])
+            layers[li].verify(x[li], flags=B.MOE_VERIFY_ACCUMULATE | B.MOE_VERIFY_ONLY_LISTED, y=yv[li], ids=idv[li])
+        cache.end_window()
+        elb.close()
+        torch.cuda.synchronize()
+        return counts
 
     def wall(fn):
         torch.cuda.synchronize()
@@ -405,54 +429,50 @@ def offload_leg(args, cfg, ctx, dev):
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3, r
 
-    # ---- copies and compute together
-    t_both, copied = [], None
-    for c in range(warm_cycles + cycles):
-        reset_tables()
-        ms, copied = wall(cycle)
+    # ---- copies and compute together, new tokens every cycle, cache carried from cycle to cycle
+    reset_residency()
+    t_both, per_cycle, fetch_log = [], [], []
+    for c in range(n_tok_sets):
+        log_c = []
+        ms, counts = wall(lambda: cycle(xs[c], True, log_c))
         if c >= warm_cycles:
             t_both.append(ms)
-        log("cycle %d: %.2f ms, %.2f GB predicted + %.2f GB on demand (%d layers)" % (c, ms, copied[0] / 1e9, copied[1] / 1e9, copied[2]))
-    n_pred = h_nm1.numpy().astype(np.int64).copy()
-    n_dem = h_nm2.numpy().astype(np.int64).copy()
-    pred_list, dem_list = h_miss1.clone(), h_miss2.clone()
-    pred_n, dem_n = h_nm1.clone(), h_nm2.clone()
+            per_cycle.append(counts)
+            fetch_log = log_c
+        log("cycle %d: %.2f ms, %d predicted + %d on demand experts fetched" % (c, ms, counts["predicted"], counts["on_demand"]))
+    hits, misses = state["cache"].stats()
+    last = n_tok_sets - 1
 
-    # ---- compute alone: everything the cycle needs is resident now (tables left as they are)
-    def compute_only():
-        draft_phase()
-        verify_phase(wait=False)
+    # ---- compute alone: the last cycle's tokens again, everything it needs is resident now
     t_compute = []
     for c in range(warm_cycles + cycles):
-        ms, _ = wall(compute_only)
+        ms, counts = wall(lambda: cycle(xs[last], True))
+        assert counts["predicted"] == 0 and counts["on_demand"] == 0, "compute-only cycle still fetches"
         if c >= warm_cycles:
             t_compute.append(ms)
-    assert int(h_nm1.sum()) == 0 and int(h_nm2.sum()) == 0, "compute-only cycle still reports missing experts"
 
-    # ---- copies alone: the same list of experts, nothing else running
+    # ---- copies alone: the last timed cycle's fetch list, nothing else running
     def copies_only():
-        base = [0] * n_layers
-        issue_copies(pred_list, pred_n, base, wait_main=False)
-        issue_copies(dem_list, dem_n, base, wait_main=False)
+        for (li, e, slot, _ev) in fetch_log:
+            ctx.expert_copy_async(layers[li].slot_view(slot), host[li][e], blob, copy_stream, None)
     t_copy = []
-    for c in range(cycles + 1):
-        reset_tables()
+    for c in range(3):
         ms, _ = wall(copies_only)
-        if c >= 1:
+        if c:
             t_copy.append(ms)
-    # leave the tables pointing at the fetched experts for the profile pass below
     tb, tc, tp = float(np.median(t_both)), float(np.median(t_compute)), float(np.median(t_copy))
-    copy_bytes = copied[0] + copied[1]
-    uniq = [len(set(idv[li].cpu().numpy().reshape(-1).tolist())) for li in range(n_layers)]
+    copy_bytes = len(fetch_log) * blob
+    uniq = [len(set(h_idv[li].reshape(-1).tolist())) for li in range(n_layers)]
     mean_u = float(np.mean(uniq))
     nbytes = algorithmic_bytes(cfg, T, mean_u)
     offload = {
-        "layers": n_layers, "resident_per_layer": n_res, "staging_slots": n_stage, "cycles": cycles,
+        "layers": n_layers, "resident_per_layer": n_res, "slots_per_layer": n_slots, "cycles": cycles,
         "t_both_ms": round(tb, 3), "t_compute_ms": round(tc, 3), "t_copy_ms": round(tp, 3),
         "overlap": round((tp + tc - tb) / min(tp, tc), 3),
-        "copy_GB_per_cycle": round(copy_bytes / 1e9, 3), "h2d_GBs": round(copy_bytes / (tp * 1e-3) / 1e9, 1),
-        "missing_predicted_per_layer": round(float(n_pred.mean()), 2),
-        "missing_on_demand_per_layer": round(float(n_dem.mean()), 2),
+        "copy_GB_last_cycle": round(copy_bytes / 1e9, 3), "h2d_GBs": round(copy_bytes / (tp * 1e-3) / 1e9, 1),
+        "fetched_predicted_per_layer": round(float(np.mean([c["predicted"] for c in per_cycle])) / n_layers, 2),
+        "fetched_on_demand_per_layer": round(float(np.mean([c["on_demand"] for c in per_cycle])) / n_layers, 2),
+        "cache_coverage_pct": round(100.0 * hits / max(hits + misses, 1), 2),
         "compute_ms_per_layer": round(tc / n_layers, 4),
     }
     log("offload:", json.dumps(offload))
@@ -461,7 +481,7 @@ def offload_leg(args, cfg, ctx, dev):
     roofline, extra = None, {"offload": offload}
     if not args.no_profile:
         ctx.profile_enable(True)
-        compute_only()
+        cycle(xs[last], True)
         torch.cuda.synchronize()
         kern = read_profile(ctx)
         ctx.profile_enable(False)
@@ -469,10 +489,33 @@ def offload_leg(args, cfg, ctx, dev):
         extra["kernels"] = table
         extra["kernel_us"] = {n: round(v["us_avg"], 2) for n, v in kern.items()}
 
-    # ---- the cycle's result on layer 0 against the oracle (same launch path as timed)
+    # ---- the Speculative Governor on what was just measured: T_draft(k) linear in k (the draft
+    # phase is token-major), T_verify(K+1) and the copy rate from this run; |E_new(k)| from the
+    # last timed cycle (against the cache as it was when that cycle began)
+    n_new = per_cycle[-1]["n_new_by_k"]
+    def draft_only():
+        for i in range(K):
+            for li, D in enumerate(layers):
+                D.draft(xs[last][li][i:i + 1], y=yd[i, li:li + 1], ids=win[i, li:li + 1], conf=wconf[i, li:li + 1])
+    draft_only()
+    t_draft_phase = min(wall(draft_only)[0] for _ in range(3)) * 1e-3
+    t_verify_stack = max(tc * 1e-3 - t_draft_phase, 1e-6)
+    gov_cfg = dict(t_draft_base=0.0, t_draft_token=t_draft_phase / K, t_pcie_init=blob / (copy_bytes / (tp * 1e-3)),
+                   t_pcie_overhead=0.0, b_pcie=copy_bytes / (tp * 1e-3), s_expert=float(blob),
+                   verify_tokens=[T], verify_seconds=[t_verify_stack], ema_alpha=0.1, p_init=0.8, k_min=1, k_max=K)
+    gov = S.Governor(gov_cfg)
+    k_star, theta_star = gov.choose_k(n_new)
+    extra["governor"] = {
+        "inputs": {kk: (round(v, 6) if isinstance(v, float) else v) for kk, v in gov_cfg.items()},
+        "n_new_by_k": n_new, "theta_by_k": [round(gov.evaluate(kk, n_new[kk])[0], 2) for kk in range(1, K + 1)],
+        "k_star": k_star, "theta_star_tokens_per_s": round(theta_star, 2),
+        "note": "acceptance probability 0.8 per token assumed (no model to measure it on); T_verify profiled at K+1 only"}
+    gov.close()
+
+    # ---- the last cycle's result on layer 0 against the oracle (same launch path as timed)
     if not args.no_cpu_baseline:
         from tests.common import oracle_arrays, oracle_verify, rel_err
-        ref = oracle_verify(oracle_arrays(L0), xs[0].cpu())
+        ref = oracle_verify(oracle_arrays(L0), xs[last][0].cpu())
         err = rel_err(yv[0].float().cpu().numpy().astype(np.float64), ref["y"])
         assert np.array_equal(idv[0].cpu().numpy(), ref["ids"]) and err <= 2e-2, "layer 0 of the cycle disagrees with the oracle"
         extra["layer0_verify_rel_err_vs_oracle"] = float("%.3e" % err)
@@ -492,6 +535,8 @@ def main():
                     help="how the timed steps are launched (per-kernel timing always runs eagerly)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--slots", type=int, default=0,
+                    help="expert-cache slots per layer for workloads with non-resident experts (0: residents + one window's union)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (known HBM traffic, for PMC scaling)")
     args = ap.parse_args()
