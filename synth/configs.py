@@ -1,12 +1,14 @@
-"""The five synthetic MoE-layer workloads (shapes of the paper's Table 1 models and of two
-further public MoE shapes).  Only shapes and distribution switches live here."""
+"""The synthetic MoE-layer workloads (shapes of the paper's Table 1 models and of two further
+public MoE shapes).  Only shapes and distribution switches live here.  Configs 1-5 are the
+benchmark's workload list; config 6 is the third model of the paper's Table 1 (the fine-grained
+shape its fused kernel is motivated by, section 3.4.3), added as a further parity workload."""
 from dataclasses import dataclass, field
 from typing import Tuple
 
 
 @dataclass(frozen=True)
 class LayerConfig:
-    index: int                 # 1..5, also the leading term of every seed
+    index: int                 # 1..6, also the leading term of every seed
     name: str
     hidden: int                # H
     n_experts: int             # E routed experts
@@ -44,6 +46,9 @@ CONFIGS = (
                 bench_layers=8),
     LayerConfig(5, "dsv2lite", 2048, 64, 1408, 6, 128, n_shared=2, verify_tokens=(6,),
                 n_layers=27, n_resident=16, bench_layers=27),
+    # Qwen1.5-MoE-A2.7B shape: 60 experts, top-4, one shared expert of 4x the width = 4 of width I
+    LayerConfig(6, "qwen15", 2048, 60, 1408, 4, 128, n_shared=4, verify_tokens=(6,), router="ar1",
+                n_layers=24, bench_layers=8),
 )
 
 
