@@ -246,39 +246,66 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
             if (!all) { if (lane == 0) s_flag = 0; continue; }
         }
-        double mx = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
-        mx = wave::max(mx);
-        // the selection compares the fp64 logits; the softmax values only have to be good to
-        // fp32, so they are computed in fp32 from the fp64 differences
-        float den = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (lane + 64 * i < E) den += expf((float)(l[i] - mx));
-        den = wave::sum(den);
-        unsigned taken = 0;
-        float sel_sum = 0.f, my_conf = 0.f;
-        int my_id = 0;
-        for (int j = 0; j < k; ++j) {
-            double bv = -INFINITY;
-            int bi = wave::kNone;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int e = lane + 64 * i;
-                if (e < E && !((taken >> i) & 1) && (bi == wave::kNone || l[i] > bv)) { bv = l[i]; bi = e; }
+        if (E <= 64) {
+            // Lane e holds logit e.  Its rank under (larger first, lower index first among equals) is
+            // counted against every logit, read from its lane with a wave-uniform index: no
+            // dependent chain of reductions per selected expert, and the order is strict, so the
+            // ranks are a permutation.
+            const double mine = l[0];
+            int rank = 0;
+            double mx = -INFINITY;
+            for (int e2 = 0; e2 < E; ++e2) {
+                const double v = wave::from_lane(mine, e2);
+                mx = fmax(mx, v);
+                rank += (v > mine || (v == mine && e2 < lane)) ? 1 : 0;
             }
-            { const wave::Best b = wave::argmax(wave::Best{bv, bi}); bv = b.v; bi = b.i; }
-            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-            const float p = expf((float)(bv - mx)) / den;
-            sel_sum += p;
-            if (lane == j) { my_conf = p; my_id = bi; }
-        }
-        if (lane < k) {
-            s_ids[t * k + lane] = my_id;
-            s_conf[t * k + lane] = my_conf;
-            s_w[t * k + lane] = a.renorm ? my_conf / sel_sum : my_conf;
-            atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
+            // the selection compares the fp64 logits; the softmax values only have to be good to
+            // fp32, so they are computed in fp32 from the fp64 differences
+            const float pe = lane < E ? expf((float)(mine - mx)) : 0.f;
+            const float conf = pe / wave::sum(pe);
+            const bool sel = lane < E && rank < k;
+            const float sel_sum = wave::sum(sel ? conf : 0.f);
+            if (sel) {
+                s_ids[t * k + rank] = lane;
+                s_conf[t * k + rank] = conf;
+                s_w[t * k + rank] = a.renorm ? conf / sel_sum : conf;
+                atomicOr(&s_mask[lane >> 6], 1ull << (lane & 63));
+            }
+        } else {
+            double mx = -INFINITY;
+    #pragma unroll
+            for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
+            mx = wave::max(mx);
+            // the selection compares the fp64 logits; the softmax values only have to be good to
+            // fp32, so they are computed in fp32 from the fp64 differences
+            float den = 0.f;
+    #pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (lane + 64 * i < E) den += expf((float)(l[i] - mx));
+            den = wave::sum(den);
+            unsigned taken = 0;
+            float sel_sum = 0.f, my_conf = 0.f;
+            int my_id = 0;
+            for (int j = 0; j < k; ++j) {
+                double bv = -INFINITY;
+                int bi = wave::kNone;
+    #pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = lane + 64 * i;
+                    if (e < E && !((taken >> i) & 1) && (bi == wave::kNone || l[i] > bv)) { bv = l[i]; bi = e; }
+                }
+                { const wave::Best b = wave::argmax(wave::Best{bv, bi}); bv = b.v; bi = b.i; }
+                if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+                const float p = expf((float)(bv - mx)) / den;
+                sel_sum += p;
+                if (lane == j) { my_conf = p; my_id = bi; }
+            }
+            if (lane < k) {
+                s_ids[t * k + lane] = my_id;
+                s_conf[t * k + lane] = my_conf;
+                s_w[t * k + lane] = a.renorm ? my_conf / sel_sum : my_conf;
+                atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
+            }
         }
     }
     __syncthreads();

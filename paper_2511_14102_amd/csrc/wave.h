@@ -44,6 +44,14 @@ __device__ inline double from_lane(double v) {
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
+// value of lane `lane` (wave-uniform, not a compile-time constant)
+__device__ inline double from_lane(double v, int lane) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), lane);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 // Largest value over the wave with its index; among equal values the lower index wins.  A lane
 // with nothing to offer passes index kNone.  (value, index) pairs are ordered strictly, so both
 // partners of a step keep the same pair.
