@@ -269,8 +269,8 @@ int moe_expert_copy_async(moe_ctx *ctx, void *dst_slot_dev, const void *src_pinn
 
 /* ---- measurement aid (not part of the method) ---------------------------------------------- */
 
-#define MOE_KERNEL_ROUTE         0   /* router logits + softmax + top-k (+ fp16 copy of x)   */
-#define MOE_KERNEL_PLAN          1   /* histogram / permutation / expert list / missing list */
+#define MOE_KERNEL_ROUTE         0   /* router logits + softmax + top-k; in the verify call the same launch also builds the plan (route_plan_kernel) */
+#define MOE_KERNEL_PLAN          1   /* histogram / permutation of moe_route_topk (perm_kernel) */
 #define MOE_KERNEL_DRAFT_FUSED   2   /* router + top-k + int4 SwiGLU experts, one launch     */
 #define MOE_KERNEL_STREAM_READ   3   /* plain streaming read (moe_stream_read_probe)         */
 #define MOE_KERNEL_BF16_GATEUP   4   /* bf16 gate+up small-M contraction, SwiGLU             */

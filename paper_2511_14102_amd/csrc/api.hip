@@ -348,8 +348,6 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
-    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
-      launch_route(s, x, wr, bias, plan->ids, plan->w, plan->conf, st); }
     PlanArgs a;
     memset(&a, 0, sizeof a);
     a.plan = plan; a.mode = 1;
@@ -359,7 +357,9 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     a.flags = flags;
     a.ids_out = ids_out;
     a.missing = missing; a.n_missing = n_missing;
-    { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_plan(s, a, st); }
+    // router and plan in one launch; its arrival counter sits behind the draft kernel's tickets
+    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
+      launch_route_plan(s, x, wr, bias, a, (uint32_t *)(ws + L.tickets + 128), st); }
     const int nexp = s.S + (s.E < s.T * s.k ? s.E : s.T * s.k);
     { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st); launch_bf16_gateup(s, plan, 0, nexp, x, ws + L.hb, nullptr, st); }
     { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);

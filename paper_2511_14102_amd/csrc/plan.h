@@ -88,6 +88,9 @@ struct PlanArgs {
     int32_t *missing; int32_t *n_missing;
 };
 void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st);
+// router + plan in one launch; arrivals: 4-byte counter in the workspace, zero between launches
+void launch_route_plan(const Shape &s, const void *x, const void *wr, const float *bias, const PlanArgs &a,
+                       uint32_t *arrivals, hipStream_t st);
 void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
                   uint64_t *mask, int32_t *list, int32_t *n_list,
                   int32_t *missing, int32_t *n_missing, hipStream_t st);

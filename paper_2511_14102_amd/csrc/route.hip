@@ -23,10 +23,21 @@ __device__ inline double bf16_to_f64(uint16_t b) {
 
 // One workgroup per token: logits of all experts (one wave per expert row at a time), then
 // wave 0 selects the top k and computes the softmax weights.
-__global__ __launch_bounds__(kRouteThreads)
-void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
-                  const float *__restrict__ bias, int H, int E, int k, int renorm,
-                  int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf)
+// kAgent: the results are stored at agent scope (another workgroup of the same launch reads them).
+template <bool kAgent, typename V>
+__device__ inline void put(V *p, V v) {
+    if (kAgent) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool kAgent, typename V>
+__device__ inline V get(const V *p) {
+    return kAgent ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+}
+
+template <bool kAgent>
+__device__ inline void route_token(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
+                                   const float *__restrict__ bias, int H, int E, int k, int renorm,
+                                   int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf)
 {
     __shared__ double s_logit[MOE_MAX_EXPERTS];
     const int t = blockIdx.x;
@@ -54,7 +65,7 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
     }
 
     __syncthreads();
-    if (wave != 0) return;
+    if (wave != 0) return;                 // (the caller's next barrier is reached by all waves)
     // each lane owns logits lane, lane + 64, lane + 128, lane + 192
     double l[4];
     double mx = -INFINITY;
@@ -90,11 +101,19 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
         if (lane == j) { my_conf = p; my_id = bi; }
     }
     if (lane < k) {
-        ids[(size_t)t * k + lane] = my_id;
+        put<kAgent>(&ids[(size_t)t * k + lane], (int32_t)my_id);
         float c = (float)my_conf;
-        if (conf) conf[(size_t)t * k + lane] = c;
-        w[(size_t)t * k + lane] = renorm ? (float)(my_conf / sel_sum) : c;
+        if (conf) put<kAgent>(&conf[(size_t)t * k + lane], c);
+        put<kAgent>(&w[(size_t)t * k + lane], renorm ? (float)(my_conf / sel_sum) : c);
     }
+}
+
+__global__ __launch_bounds__(kRouteThreads)
+void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
+                  const float *__restrict__ bias, int H, int E, int k, int renorm,
+                  int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf)
+{
+    route_token<false>(x, wr, bias, H, E, k, renorm, ids, w, conf);
 }
 
 // count / off / perm for n assignments over E experts; one workgroup, results in `count`,
@@ -136,8 +155,8 @@ void perm_kernel(const int32_t *__restrict__ ids, int n, int E, int32_t *count, 
 // Builds the execution plan: histogram / permutation, the list of experts to run (shared
 // experts at active indices [0, S), then present routed experts ascending), their weight
 // pointers and row ranges, the per-row token / weight / live flags, and the missing list.
-__global__ __launch_bounds__(256)
-void plan_kernel(Plan *__restrict__ plan, int T, int E, int k, int S, int mode,
+template <bool kAgent>
+__device__ inline void plan_body(Plan *__restrict__ plan, int T, int E, int k, int S, int mode,
                  const char *w0, size_t stride0, const char *w1, size_t stride1,
                  const int32_t *__restrict__ slot_of_expert,
                  const char *shared, size_t shared_stride, int flags,
@@ -152,10 +171,10 @@ void plan_kernel(Plan *__restrict__ plan, int T, int E, int k, int S, int mode,
     const bool only_listed = (flags & MOE_VERIFY_ONLY_LISTED) != 0;
 
     for (int a = threadIdx.x; a < n; a += blockDim.x) {
-        int id = plan->ids[a];
+        int id = get<kAgent>(&plan->ids[a]);
         s_ids[a] = id;
         if (ids_out) ids_out[a] = id;
-        if (conf_out) conf_out[a] = plan->conf[a];
+        if (conf_out) conf_out[a] = get<kAgent>(&plan->conf[a]);
     }
     for (int e = threadIdx.x; e < E; e += blockDim.x) {
         s_slot[e] = mode == 0 ? e : slot_of_expert[e];
@@ -217,7 +236,7 @@ void plan_kernel(Plan *__restrict__ plan, int T, int E, int k, int S, int mode,
         int a = plan->perm[pos];
         int e = s_ids[a];
         plan->row_tok[pos] = a / k;
-        plan->row_w[pos] = plan->w[a];
+        plan->row_w[pos] = get<kAgent>(&plan->w[a]);
         plan->row_live[pos] = (s_listed[e] && s_slot[e] >= 0) ? 1 : 0;
     }
     if (threadIdx.x == 0) {
@@ -227,6 +246,44 @@ void plan_kernel(Plan *__restrict__ plan, int T, int E, int k, int S, int mode,
         plan->n_missing = s_nmiss;
         if (n_missing) *n_missing = s_nmiss;
     }
+}
+
+struct PlanKernelArgs {
+    Plan *plan; int T, E, k, S, mode;
+    const char *w0; size_t stride0; const char *w1; size_t stride1;
+    const int32_t *slot_of_expert; const char *shared; size_t shared_stride; int flags;
+    int32_t *ids_out; float *conf_out; int32_t *missing; int32_t *n_missing;
+};
+
+__global__ __launch_bounds__(256)
+void plan_kernel(const PlanKernelArgs a)
+{
+    plan_body<false>(a.plan, a.T, a.E, a.k, a.S, a.mode, a.w0, a.stride0, a.w1, a.stride1, a.slot_of_expert,
+                     a.shared, a.shared_stride, a.flags, a.ids_out, a.conf_out, a.missing, a.n_missing);
+}
+
+// Router and plan in one launch (the verify call): one workgroup per token routes it and stores
+// ids / weights / confidences at agent scope, waits for its stores, and takes a number; the
+// workgroup that takes the last number has everybody's results in reach (agent-scope loads) and
+// builds the plan.  `arrivals` is a counter in the workspace that is zero between launches.
+__global__ __launch_bounds__(kRouteThreads)
+void route_plan_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
+                       const float *__restrict__ bias, int H, int renorm, const PlanKernelArgs a,
+                       uint32_t *arrivals)
+{
+    __shared__ int s_last;
+    route_token<true>(x, wr, bias, H, a.E, a.k, renorm, a.plan->ids, a.plan->w, a.plan->conf);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this thread's stores have been performed
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t n = __hip_atomic_fetch_add(arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = n == gridDim.x - 1;
+        if (s_last) __hip_atomic_store(arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    plan_body<true>(a.plan, a.T, a.E, a.k, a.S, a.mode, a.w0, a.stride0, a.w1, a.stride1, a.slot_of_expert,
+                    a.shared, a.shared_stride, a.flags, a.ids_out, a.conf_out, a.missing, a.n_missing);
 }
 
 // Union of expert ids: bitmask in shared memory, then ordered compaction by one wave.
@@ -278,12 +335,26 @@ void launch_perm(const Shape &s, const int32_t *ids, int32_t *count, int32_t *of
     launch(perm_kernel, dim3(1), dim3(256), 0, st, ids, s.T * s.k, s.E, count, off, perm);
 }
 
+static PlanKernelArgs plan_kernel_args(const Shape &s, const PlanArgs &a)
+{
+    PlanKernelArgs k;
+    k.plan = a.plan; k.T = s.T; k.E = s.E; k.k = s.k; k.S = s.S; k.mode = a.mode;
+    k.w0 = (const char *)a.w0; k.stride0 = a.stride0; k.w1 = (const char *)a.w1; k.stride1 = a.stride1;
+    k.slot_of_expert = a.slot_of_expert; k.shared = (const char *)a.shared; k.shared_stride = a.shared_stride;
+    k.flags = a.flags; k.ids_out = a.ids_out; k.conf_out = a.conf_out; k.missing = a.missing; k.n_missing = a.n_missing;
+    return k;
+}
+
 void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st)
 {
-    launch(plan_kernel, dim3(1), dim3(256), 0, st, a.plan, s.T, s.E, s.k, s.S, a.mode,
-                       (const char *)a.w0, a.stride0, (const char *)a.w1, a.stride1,
-                       a.slot_of_expert, (const char *)a.shared, a.shared_stride, a.flags,
-                       a.ids_out, a.conf_out, a.missing, a.n_missing);
+    launch(plan_kernel, dim3(1), dim3(256), 0, st, plan_kernel_args(s, a));
+}
+
+void launch_route_plan(const Shape &s, const void *x, const void *wr, const float *bias, const PlanArgs &a,
+                       uint32_t *arrivals, hipStream_t st)
+{
+    launch(route_plan_kernel, dim3(s.T), dim3(kRouteThreads), 0, st, (const uint16_t *)x, (const uint16_t *)wr,
+           bias, s.H, s.renorm, plan_kernel_args(s, a), arrivals);
 }
 
 void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
