@@ -351,3 +351,26 @@ def test_graph_replays_match_eager_calls(ctx, tiny):
         assert torch.equal(got[2], e_v["y"])
         ref = oracle_draft(tiny.A, x[:1])
         assert np.array_equal(to_np(got[1]), ref["ids"]) and rel_err(to_np(got[0]), ref["y"]) <= TOL_DRAFT
+
+
+def test_mixed_token_counts_share_one_workspace(ctx, tiny):
+    """Draft and verify calls of changing token counts on one layer / one workspace: the counters
+    the kernels leave in the workspace (tickets, arrivals, tagged slots) must be back in their idle
+    state after every call whatever the grid of the previous one was."""
+    cfg, D = tiny.cfg, tiny.D
+    rng = np.random.default_rng(7)
+    for it in range(24):
+        T = int(rng.integers(1, 9))
+        x = tokens_with_clear_routing(cfg, tiny.A, T, step=300 + it)
+        if it % 3 != 2:
+            ref = oracle_draft(tiny.A, x)
+            r = D.draft(x.cuda())
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(r["ids"]), ref["ids"]), (it, T)
+            assert rel_err(to_np(r["y"]), ref["y"]) <= TOL_DRAFT, (it, T)
+        else:
+            ref = oracle_verify(tiny.A, x)
+            r = D.verify(x.cuda())
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(r["ids"]), ref["ids"]), (it, T)
+            assert rel_err(to_np(r["y"]), ref["y"]) <= TOL_VERIFY, (it, T)
