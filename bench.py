@@ -256,6 +256,21 @@ def resident_leg(args, cfg, ctx, dev):
         }
         extra["per_call"]["verify_tokens_per_s"] = round(T * 1e6 / extra["per_call"]["verify_us"], 1)
 
+    # ---- layer 0's step as the timed launches left it, against the oracle (same buffers, same path)
+    if not args.no_cpu_baseline:
+        from tests.common import oracle_arrays, oracle_draft, oracle_verify, rel_err
+        step(0)
+        torch.cuda.synchronize()
+        A0 = oracle_arrays(L0)
+        x0 = xs[0].cpu()
+        rd, rv = oracle_draft(A0, x0[:K]), oracle_verify(A0, x0)
+        b0 = bufs[0]
+        e_d = rel_err(b0["yd"].cpu().numpy().astype(np.float64), rd["y"])
+        e_v = rel_err(b0["yv"].float().cpu().numpy().astype(np.float64), rv["y"])
+        assert np.array_equal(b0["win"].cpu().numpy(), rd["ids"]) and np.array_equal(b0["idv"].cpu().numpy(), rv["ids"]), \
+            "layer 0 routing disagrees with the oracle"
+        assert e_d <= 1e-3 and e_v <= 2e-2, "layer 0 outputs disagree with the oracle: %g %g" % (e_d, e_v)
+        extra["layer0_rel_err_vs_oracle"] = {"draft": float("%.3e" % e_d), "verify": float("%.3e" % e_v)}
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, L0, K, T)
     emit(cfg, args, K, T, n_layers, ms_step, ms_eager, launch, mean_u, nbytes, roofline, cpu, extra)
 
