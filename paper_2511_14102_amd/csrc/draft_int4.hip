@@ -39,6 +39,7 @@
 //   4. the workgroup holding the last ticket (everybody has finished polling by then) clears
 //      the tags and the ticket counters at its end, so the workspace is back in its idle state
 //      when the kernel ends.  This also holds when the same launch is replayed from a HIP graph.
+#include <type_traits>
 #include "plan.h"
 #include "wave.h"
 
@@ -134,8 +135,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     // tiles a wave keeps in flight (rolling windows), sized so that no instantiation spills:
     // two workgroups per CU leave 128 VGPRs per wave for MT <= 2
     constexpr int kGuWin = MT == 1 ? (UPG == 4 ? 8 : 4) : (MT == 2 ? 4 : 8);
-    constexpr int kDownWin = MT == 1 && UPG == 4 ? 8 : 4;
-    constexpr int kInLoop = kDownWin < kGuWin / 2 ? kDownWin : kGuWin / 2;   // down tiles requested inside the last gate/up window
     constexpr int kSzWin = kGuWin / UPG;
     __shared__ double s_part[kWaves];
     __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
@@ -387,13 +386,26 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             rw[i] = s_w[arow];
         }
 
-        // down tiles of this wave: row tiles wave, wave + 8, ...  Their loads do not depend on h:
-        // the codes are requested while the last gate/up window is consumed (taking over its
-        // registers, and queueing behind the gate/up data), the scales right after it.
+        // ---- this wave's tile stream: its gate/up tiles u0 .. u1 (K = H split over the waves by
+        // groups), padded to whole windows, then its down row tiles wave, wave + 8, ... (their loads
+        // do not depend on h).  A rolling window of kGuWin tiles is in flight.  EVERY load of the
+        // stream is unconditional: past the end of a part its address is clamped to the part's
+        // last tile.  The compiler counts the loads in flight in program order; a load under a
+        // branch makes it wait for all of them wherever it needs one, which empties the window.
         const int nrt = H / 64;
-        u32x4 dq[kDownWin], dsz[kDownWin];
-
-        // ---- gate / up: K = H split over the waves by groups; rolling window of kGuWin tiles
+        const int u0 = ((wave * G) / kWaves) * UPG, u1 = (((wave + 1) * G) / kWaves) * UPG;
+        const int nt = u1 - u0;
+        const int ntp = (nt + kGuWin - 1) / kGuWin * kGuWin;
+        const int rt_last = wave < nrt ? wave + ((nrt - 1 - wave) / kWaves) * kWaves : 0;
+        const int g_last = nt > 0 ? (u1 - 1) / UPG : 0;
+        auto stream_ptr = [&](int p) -> const u32x4 * {            // p: position in the stream
+            const int ku = u0 + p;
+            const int rt = wave + (p - ntp) * kWaves;
+            const u32x4 *gp = qgu + (size_t)(ku < u1 ? ku : u1 - 1) * 64;
+            const u32x4 *dp = qd + (size_t)(rt < nrt ? rt : rt_last) * 64;
+            return p < ntp ? gp : dp;
+        };
+        auto gsz_ptr = [&](int gi) { return szgu + (size_t)(gi < g_last ? gi : g_last) * 16; };
         float tot[4][NI];
         f32x4 acc[4];
 #pragma unroll
@@ -402,29 +414,22 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
             for (int i = 0; i < NI; ++i) tot[d][i] = 0.f;
         }
-        const int u0 = ((wave * G) / kWaves) * UPG, u1 = (((wave + 1) * G) / kWaves) * UPG;
-        u32x4 gq[kGuWin], gsz[kSzWin];
+        u32x4 win[kGuWin], gsz[kSzWin];
 #pragma unroll
-        for (int i = 0; i < kGuWin; ++i)
-            if (u0 + i < u1) gq[i] = __builtin_nontemporal_load(qgu + (size_t)(u0 + i) * 64);
+        for (int i = 0; i < kGuWin; ++i) win[i] = __builtin_nontemporal_load(stream_ptr(i));
 #pragma unroll
-        for (int i = 0; i < kSzWin; ++i)
-            if (u0 + i * UPG < u1) gsz[i] = __builtin_nontemporal_load(szgu + (size_t)(u0 / UPG + i) * 16);
+        for (int i = 0; i < kSzWin; ++i) gsz[i] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG + i));
         draw_ticket();
-        u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (u0 < u1 ? u0 : 0) * 32);
-        bool down_issued = false;
-        for (int base = u0; base < u1; base += kGuWin) {
-            const bool last = base + kGuWin >= u1;
+        u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (nt > 0 ? u0 : 0) * 32);
+        for (int base = 0; base < ntp; base += kGuWin) {
 #pragma unroll
             for (int i = 0; i < kGuWin; ++i) {
-                const int ku = base + i;
-                if (last && (i & 1) && (i >> 1) < kInLoop) {
-                    const int rt = wave + (i >> 1) * kWaves;
-                    if (rt < nrt) dq[i >> 1] = __builtin_nontemporal_load(qd + (size_t)rt * 64);
-                }
+                const int pz = base + i, ku = u0 + pz;
+                const u32x4 qv = win[i];
+                win[i] = __builtin_nontemporal_load(stream_ptr(pz + kGuWin));
+                u32x4 szv = gsz[i / UPG];
+                if (i % UPG == UPG - 1) gsz[i / UPG] = __builtin_nontemporal_load(gsz_ptr(ku / UPG + kSzWin));
                 if (ku < u1) {
-                    const u32x4 qv = gq[i];
-                    if (ku + kGuWin < u1) gq[i] = __builtin_nontemporal_load(qgu + (size_t)(ku + kGuWin) * 64);
                     const u32x4 xn = *reinterpret_cast<const u32x4 *>(xrow + (ku + 1 < u1 ? ku + 1 : ku) * 32);
                     acc[0] = mfma(xa, unpack8(qv.x, uk), acc[0]);
                     acc[1] = mfma(xa, unpack8(qv.y, uk), acc[1]);
@@ -433,8 +438,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     xa = xn;
                     if (i % UPG == UPG - 1) {                 // end of a group: scale / zero / offset
                         const int gi = ku / UPG;
-                        const u32x4 szv = gsz[i / UPG];
-                        if (ku + kGuWin < u1) gsz[i / UPG] = __builtin_nontemporal_load(szgu + (size_t)(gi + kSzWin) * 16);
                         const uint32_t sw[4] = {szv.x, szv.y, szv.z, szv.w};
                         float xs[NI];
 #pragma unroll
@@ -450,15 +453,13 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     }
                 }
             }
-            down_issued = last;
         }
+        // the window now holds this wave's first kGuWin down tiles; their scales follow
+        u32x4 dsz[kGuWin];
 #pragma unroll
-        for (int i = 0; i < kDownWin; ++i) {
+        for (int i = 0; i < kGuWin; ++i) {
             const int rt = wave + i * kWaves;
-            if (rt < nrt) {
-                if (!down_issued || i >= kInLoop) dq[i] = __builtin_nontemporal_load(qd + (size_t)rt * 64);
-                dsz[i] = __builtin_nontemporal_load(szd + (size_t)rt * 16);
-            }
+            dsz[i] = __builtin_nontemporal_load(szd + (size_t)(rt < nrt ? rt : rt_last) * 16);
         }
         if (c < NC) {
 #pragma unroll
@@ -508,17 +509,20 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             tokd[i] = arow / k;
             rwd[i] = s_w[arow];
         }
-        for (int j0 = 0; wave + j0 * kWaves < nrt; j0 += kDownWin) {
+        // one pass over the window: kReload: the slot is refilled with the tile kGuWin further on
+        // (clamped, unconditional); the last pass refills nothing
+        auto down_pass = [&](int j0, auto reload) {
+            constexpr bool kReload = decltype(reload)::value;
 #pragma unroll
-            for (int i = 0; i < kDownWin; ++i) {
+            for (int i = 0; i < kGuWin; ++i) {
                 const int rt = wave + (j0 + i) * kWaves;
+                const u32x4 qv = win[i], szv = dsz[i];
+                if (kReload) {
+                    const int rtn = rt + kGuWin * kWaves;
+                    win[i] = __builtin_nontemporal_load(qd + (size_t)(rtn < nrt ? rtn : rt_last) * 64);
+                    dsz[i] = __builtin_nontemporal_load(szd + (size_t)(rtn < nrt ? rtn : rt_last) * 16);
+                }
                 if (rt < nrt) {
-                    const u32x4 qv = dq[i], szv = dsz[i];
-                    const int rtn = rt + kDownWin * kWaves;
-                    if (rtn < nrt) {
-                        dq[i] = __builtin_nontemporal_load(qd + (size_t)rtn * 64);
-                        dsz[i] = __builtin_nontemporal_load(szd + (size_t)rtn * 16);
-                    }
                     const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, sw[4] = {szv.x, szv.y, szv.z, szv.w};
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
@@ -539,7 +543,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     }
                 }
             }
-        }
+        };
+        const int ndw = wave < nrt ? (nrt - 1 - wave) / kWaves + 1 : 0;      // this wave's row tiles
+        int j0 = 0;
+        for (; j0 + kGuWin < ndw; j0 += kGuWin) down_pass(j0, std::true_type{});
+        down_pass(j0, std::false_type{});
     }
 
     else {
