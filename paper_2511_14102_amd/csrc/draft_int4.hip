@@ -134,7 +134,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     constexpr int NC = MT > 4 ? 2 : 1;           // lane groups (of 16) whose D rows can be valid
     // tiles a wave keeps in flight (rolling windows), sized so that no instantiation spills:
     // two workgroups per CU leave 128 VGPRs per wave for MT <= 2
-    constexpr int kGuWin = MT == 1 ? (UPG == 4 ? 8 : 4) : (MT == 2 ? 4 : 8);
+    constexpr int kGuWin = MT == 1 ? (UPG >= 2 ? 8 : 4) : (MT == 2 ? 4 : 8);
     constexpr int kSzWin = kGuWin / UPG;
     __shared__ double s_part[kWaves];
     __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
@@ -396,16 +396,29 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         const int u0 = ((wave * G) / kWaves) * UPG, u1 = (((wave + 1) * G) / kWaves) * UPG;
         const int nt = u1 - u0;
         const int ntp = (nt + kGuWin - 1) / kGuWin * kGuWin;
-        const int rt_last = wave < nrt ? wave + ((nrt - 1 - wave) / kWaves) * kWaves : 0;
+        const int r0 = (wave * nrt) / kWaves, r1 = ((wave + 1) * nrt) / kWaves;   // this wave's down row tiles
+        const int rt_last = r1 > r0 ? r1 - 1 : 0;
         const int g_last = nt > 0 ? (u1 - 1) / UPG : 0;
         auto stream_ptr = [&](int p) -> const u32x4 * {            // p: position in the stream
             const int ku = u0 + p;
-            const int rt = wave + (p - ntp) * kWaves;
+            const int rt = r0 + (p - ntp);
             const u32x4 *gp = qgu + (size_t)(ku < u1 ? ku : u1 - 1) * 64;
-            const u32x4 *dp = qd + (size_t)(rt < nrt ? rt : rt_last) * 64;
+            const u32x4 *dp = qd + (size_t)(rt < r1 ? rt : rt_last) * 64;
             return p < ntp ? gp : dp;
         };
-        auto gsz_ptr = [&](int gi) { return szgu + (size_t)(gi < g_last ? gi : g_last) * 16; };
+        // Scale/zero entries are fetched four groups (or four row tiles) per load: lane group c
+        // takes the 16 bytes of row r of group first + 4 pk + c, and a lane picks the entry of
+        // the group at hand from that lane group with a lane permute.
+        constexpr int kSzPacks = (kSzWin + 3) / 4;
+        auto gsz_ptr = [&](int first, int pk) {
+            const int gi = first + 4 * pk + c;
+            return szgu + (size_t)(gi < g_last ? gi : g_last) * 16;
+        };
+        auto pick = [&](const u32x4 &v, int from) {               // the entry held by lane group `from`, row r
+            const int src = from * 16 + r;
+            return (u32x4){(uint32_t)__shfl((int)v.x, src, 64), (uint32_t)__shfl((int)v.y, src, 64),
+                           (uint32_t)__shfl((int)v.z, src, 64), (uint32_t)__shfl((int)v.w, src, 64)};
+        };
         float tot[4][NI];
         f32x4 acc[4];
 #pragma unroll
@@ -414,21 +427,23 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
             for (int i = 0; i < NI; ++i) tot[d][i] = 0.f;
         }
-        u32x4 win[kGuWin], gsz[kSzWin];
+        u32x4 win[kGuWin], gsz[kSzPacks];
 #pragma unroll
         for (int i = 0; i < kGuWin; ++i) win[i] = __builtin_nontemporal_load(stream_ptr(i));
 #pragma unroll
-        for (int i = 0; i < kSzWin; ++i) gsz[i] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG + i));
+        for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG, pk));
         draw_ticket();
         u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (nt > 0 ? u0 : 0) * 32);
         for (int base = 0; base < ntp; base += kGuWin) {
+            u32x4 gsz_next[kSzPacks];                             // the next window's groups
+#pragma unroll
+            for (int pk = 0; pk < kSzPacks; ++pk)
+                gsz_next[pk] = __builtin_nontemporal_load(gsz_ptr((u0 + base) / UPG + kSzWin, pk));
 #pragma unroll
             for (int i = 0; i < kGuWin; ++i) {
                 const int pz = base + i, ku = u0 + pz;
                 const u32x4 qv = win[i];
                 win[i] = __builtin_nontemporal_load(stream_ptr(pz + kGuWin));
-                u32x4 szv = gsz[i / UPG];
-                if (i % UPG == UPG - 1) gsz[i / UPG] = __builtin_nontemporal_load(gsz_ptr(ku / UPG + kSzWin));
                 if (ku < u1) {
                     const u32x4 xn = *reinterpret_cast<const u32x4 *>(xrow + (ku + 1 < u1 ? ku + 1 : ku) * 32);
                     acc[0] = mfma(xa, unpack8(qv.x, uk), acc[0]);
@@ -438,6 +453,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     xa = xn;
                     if (i % UPG == UPG - 1) {                 // end of a group: scale / zero / offset
                         const int gi = ku / UPG;
+                        const u32x4 szv = pick(gsz[(i / UPG) / 4], (i / UPG) % 4);
                         const uint32_t sw[4] = {szv.x, szv.y, szv.z, szv.w};
                         float xs[NI];
 #pragma unroll
@@ -453,14 +469,18 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     }
                 }
             }
+#pragma unroll
+            for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = gsz_next[pk];
         }
         // the window now holds this wave's first kGuWin down tiles; their scales follow
-        u32x4 dsz[kGuWin];
+        constexpr int kDPacks = (kGuWin + 3) / 4;
+        auto dsz_ptr = [&](int first, int pk) {
+            const int rt = first + 4 * pk + c;
+            return szd + (size_t)(rt < r1 ? rt : rt_last) * 16;
+        };
+        u32x4 dsz[kDPacks];
 #pragma unroll
-        for (int i = 0; i < kGuWin; ++i) {
-            const int rt = wave + i * kWaves;
-            dsz[i] = __builtin_nontemporal_load(szd + (size_t)(rt < nrt ? rt : rt_last) * 16);
-        }
+        for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = __builtin_nontemporal_load(dsz_ptr(r0, pk));
         if (c < NC) {
 #pragma unroll
             for (int d = 0; d < 4; ++d)
@@ -513,16 +533,22 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         // (clamped, unconditional); the last pass refills nothing
         auto down_pass = [&](int j0, auto reload) {
             constexpr bool kReload = decltype(reload)::value;
+            u32x4 dsz_next[kDPacks];
+            if (kReload) {
+#pragma unroll
+                for (int pk = 0; pk < kDPacks; ++pk)
+                    dsz_next[pk] = __builtin_nontemporal_load(dsz_ptr(r0 + j0 + kGuWin, pk));
+            }
 #pragma unroll
             for (int i = 0; i < kGuWin; ++i) {
-                const int rt = wave + (j0 + i) * kWaves;
-                const u32x4 qv = win[i], szv = dsz[i];
+                const int rt = r0 + j0 + i;
+                const u32x4 qv = win[i];
                 if (kReload) {
-                    const int rtn = rt + kGuWin * kWaves;
-                    win[i] = __builtin_nontemporal_load(qd + (size_t)(rtn < nrt ? rtn : rt_last) * 64);
-                    dsz[i] = __builtin_nontemporal_load(szd + (size_t)(rtn < nrt ? rtn : rt_last) * 16);
+                    const int rtn = rt + kGuWin;
+                    win[i] = __builtin_nontemporal_load(qd + (size_t)(rtn < r1 ? rtn : rt_last) * 64);
                 }
-                if (rt < nrt) {
+                if (rt < r1) {
+                    const u32x4 szv = pick(dsz[i / 4], i % 4);
                     const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, sw[4] = {szv.x, szv.y, szv.z, szv.w};
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
@@ -543,8 +569,12 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     }
                 }
             }
+            if (kReload) {
+#pragma unroll
+                for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = dsz_next[pk];
+            }
         };
-        const int ndw = wave < nrt ? (nrt - 1 - wave) / kWaves + 1 : 0;      // this wave's row tiles
+        const int ndw = r1 - r0;
         int j0 = 0;
         for (; j0 + kGuWin < ndw; j0 += kGuWin) down_pass(j0, std::true_type{});
         down_pass(j0, std::false_type{});
