@@ -511,20 +511,38 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
         __syncthreads();
 
-        // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns
-        // A rows 2t and 2t + 1 are the hi and the lo part of token slot t, so one MFMA yields
-        // both products and a token's output is the sum of two D registers of one lane: lane
-        // group c holds token slots 2c and 2c + 1
-        constexpr int ND = MT < 2 ? 1 : 2;           // token slots per lane
-        constexpr int NCD = (MT + 1) / 2;            // lane groups with valid slots
-        const int hslot = (r >> 1) < cnt ? (r >> 1) : 0;
-        const u32x4 ha = *reinterpret_cast<const u32x4 *>((r & 1) ? &s_hlo[hslot][c * 8] : &s_hhi[hslot][c * 8]);
+        // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns.
+        // The hi and the lo part of h of a token slot are two A rows, so one MFMA yields both
+        // products.  With few token slots the 16 A rows have room for more: the tile's row block
+        // bl gets its own copy of the h rows at A rows bl * kRs .. (all other rows zero), and the
+        // kBpa MFMAs of kBpa row blocks accumulate into ONE D tile, whose lane group(s) bl then
+        // hold row block bl.  For one or two tokens that is the whole tile (64 outputs) in one D
+        // register pair per token: one 64-lane atomic per token and tile instead of four 16-lane ones.
+        constexpr int kBpa = MT <= 2 ? 4 : (MT == 4 ? 2 : 1);    // row blocks per accumulated D tile
+        constexpr int kRs = 16 / kBpa;                           // A rows per row block
+        constexpr int kLgb = 4 / kBpa;                           // lane groups per row block
+        constexpr int ND = MT < 2 ? 1 : 2;                       // token slots per lane
+        u32x4 hab[kBpa];
+        {
+            const int within = r % kRs, slot = (within >> 1) < cnt ? (within >> 1) : 0;
+            const u32x4 hv = *reinterpret_cast<const u32x4 *>((within & 1) ? &s_hlo[slot][c * 8] : &s_hhi[slot][c * 8]);
+            const bool used = within < 2 * MT;
+#pragma unroll
+            for (int bl = 0; bl < kBpa; ++bl) {
+                const bool on = used && r / kRs == bl;
+                hab[bl] = (u32x4){on ? hv.x : 0u, on ? hv.y : 0u, on ? hv.z : 0u, on ? hv.w : 0u};
+            }
+        }
+        const int my_bl = c / kLgb;                              // the row block this lane's D registers hold
         float hsum[ND], rwd[ND];
         int tokd[ND];
+        bool live[ND];
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-            const int slot = 2 * c + i < cnt ? 2 * c + i : 0;
+            const int t = 2 * (c % kLgb) + i;
+            const int slot = t < cnt ? t : 0;
             const int arow = s_row_a[slot];
+            live[i] = t < cnt;
             hsum[i] = s_hsum[slot];
             tokd[i] = arow / k;
             rwd[i] = s_w[arow];
@@ -551,19 +569,20 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     const u32x4 szv = pick(dsz[i / 4], i % 4);
                     const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, sw[4] = {szv.x, szv.y, szv.z, szv.w};
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const bf16x8 b = unpack8(qw[d], uk);
-                        const f32x4 o = mfma(ha, b, (f32x4){0.f, 0.f, 0.f, 0.f});
-                        const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] & 0xffff));
-                        const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] >> 16)) + 128.f;
-                        if (c < NCD) {
+                    for (int q = 0; q < 4 / kBpa; ++q) {
+                        f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                            for (int j = 0; j < ND; ++j) {
-                                if (2 * c + j < cnt) {
-                                    const float val = sc * ((o[2 * j] + o[2 * j + 1]) - zp * hsum[j]) * rwd[j];
-                                    __hip_atomic_fetch_add(&a.y[(size_t)tokd[j] * H + rt * 64 + d * 16 + r], val,
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                }
+                        for (int bl = 0; bl < kBpa; ++bl) o = mfma(hab[bl], unpack8(qw[q * kBpa + bl], uk), o);
+                        const int d = q * kBpa + my_bl;          // this lane's row block of the tile
+                        const uint32_t swd = d == 0 ? sw[0] : (d == 1 ? sw[1] : (d == 2 ? sw[2] : sw[3]));
+                        const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(swd & 0xffff));
+                        const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(swd >> 16)) + 128.f;
+#pragma unroll
+                        for (int j = 0; j < ND; ++j) {
+                            if (live[j]) {
+                                const float val = sc * ((o[2 * j] + o[2 * j + 1]) - zp * hsum[j]) * rwd[j];
+                                __hip_atomic_fetch_add(&a.y[(size_t)tokd[j] * H + rt * 64 + d * 16 + r], val,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             }
                         }
                     }
