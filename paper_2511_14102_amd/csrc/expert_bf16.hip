@@ -17,6 +17,9 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+// Weight pointers come out of the plan as integers; they are device (global) memory.  Saying so
+// keeps the loads from being FLAT ones, which count on two counters and force full waits.
+typedef const __attribute__((address_space(1))) u32x4 *wptr;
 
 constexpr int kWaves = 4;          // K-split inside a workgroup
 constexpr int kUnroll = 8;         // tiles in flight per wave and matrix
@@ -51,8 +54,8 @@ void bf16_gateup_kernel(const Plan *__restrict__ plan, int first_active,
     const int n = lane & 15, c = lane >> 4;
     const int U = H / 32;
     const size_t mat = (size_t)(I / 16) * U * 64;              // uint4 per matrix
-    const u32x4 *wg = reinterpret_cast<const u32x4 *>(plan->act_w0[u]) + (size_t)blockIdx.x * U * 64 + lane;
-    const u32x4 *wu = wg + mat;
+    const wptr wg = (wptr)(plan->act_w0[u]) + (size_t)blockIdx.x * U * 64 + lane;
+    const wptr wu = wg + mat;
     const int tok = n < cnt ? plan->row_tok[off + n] : -1;
     const uint16_t *xrow = x + (size_t)(tok < 0 ? 0 : tok) * H + c * 8;
     const int ku0 = (wave * U) / kWaves, ku1 = ((wave + 1) * U) / kWaves;
@@ -127,7 +130,7 @@ void bf16_down_kernel(const Plan *__restrict__ plan, int first_active,
     const int n = lane & 15, c = lane >> 4;
     const int U = I / 32;
     const size_t mat = (size_t)(I / 16) * (H / 32) * 64;
-    const u32x4 *wd = reinterpret_cast<const u32x4 *>(plan->act_w0[u]) + 2 * mat + (size_t)blockIdx.x * U * 64 + lane;
+    const wptr wd = (wptr)(plan->act_w0[u]) + 2 * mat + (size_t)blockIdx.x * U * 64 + lane;
     const bool live = n < cnt;
     const size_t hoff = (size_t)(off + (live ? n : 0)) * I + c * 8;
     const uint16_t *hrow = hb + hoff;
