@@ -18,7 +18,7 @@
 // KiB of codes), not by HBM; the matrix pipe takes the multiply-adds off them at no cost and
 // makes several tokens per call free.  Scale, zero and the 128 offset are applied once per
 // group on the accumulators.  Activations stay bf16 (exact); the SwiGLU intermediate is carried
-// as a bf16 hi + lo pair (16 significant bits, two MFMAs).
+// as a bf16 hi + lo pair (16 significant bits) that occupies two A rows of the same MFMA.
 //
 // Work decomposition ("slice fusion").  A work item is (expert, slice of 32 intermediate
 // rows): its workgroup computes the 32 gate and 32 up pre-activations (K = H split over the 8
