@@ -132,9 +132,9 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 {
     constexpr int NI = MT < 4 ? MT : 4;          // D rows (tokens) per lane that can be valid
     constexpr int NC = MT > 4 ? 2 : 1;           // lane groups (of 16) whose D rows can be valid
-    // tiles a wave keeps in flight (rolling windows), sized so that no instantiation spills:
-    // two workgroups per CU leave 128 VGPRs per wave for MT <= 2
-    constexpr int kGuWin = MT == 1 ? (UPG >= 2 ? 8 : 4) : (MT == 2 ? 4 : 8);
+    // tiles a wave keeps in flight (rolling window); no instantiation spills with 8 (two
+    // workgroups per CU leave 128 VGPRs per wave for MT <= 2)
+    constexpr int kGuWin = 8;
     constexpr int kSzWin = kGuWin / UPG;
     __shared__ double s_part[kWaves];
     __shared__ int32_t s_ids[MOE_MAX_ASSIGN];
