@@ -66,6 +66,30 @@ __device__ inline void route_token(const uint16_t *__restrict__ x, const uint16_
 
     __syncthreads();
     if (wave != 0) return;                 // (the caller's next barrier is reached by all waves)
+    if (E <= 64) {
+        // Lane e holds logit e; its rank under (larger first, lower index first among equals) is
+        // counted against every logit read from its lane with a wave-uniform index.  The order
+        // is strict, so the ranks are a permutation and rank < k is the selection.
+        const double mine = lane < E ? s_logit[lane] : -INFINITY;
+        int rank = 0;
+        double mx = -INFINITY;
+        for (int e2 = 0; e2 < E; ++e2) {
+            const double v = wave::from_lane(mine, e2);
+            mx = fmax(mx, v);
+            rank += (v > mine || (v == mine && e2 < lane)) ? 1 : 0;
+        }
+        const double pe = lane < E ? exp(mine - mx) : 0.0;
+        const double p = pe / wave::sum(pe);
+        const bool sel = lane < E && rank < k;
+        const double sel_sum = wave::sum(sel ? p : 0.0);
+        if (sel) {
+            put<kAgent>(&ids[(size_t)t * k + rank], (int32_t)lane);
+            const float c = (float)p;
+            if (conf) put<kAgent>(&conf[(size_t)t * k + rank], c);
+            put<kAgent>(&w[(size_t)t * k + rank], renorm ? (float)(p / sel_sum) : c);
+        }
+        return;
+    }
     // each lane owns logits lane, lane + 64, lane + 128, lane + 192
     double l[4];
     double mx = -INFINITY;
