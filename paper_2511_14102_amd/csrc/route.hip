@@ -190,6 +190,8 @@ __device__ inline void plan_body(Plan *__restrict__ plan, int T, int E, int k, i
     __shared__ int32_t s_count[MOE_MAX_EXPERTS];
     __shared__ int32_t s_slot[MOE_MAX_EXPERTS];
     __shared__ unsigned char s_listed[MOE_MAX_EXPERTS];
+    __shared__ int32_t s_off[MOE_MAX_EXPERTS + 1];     // offsets and permutation stay in LDS for the
+    __shared__ int32_t s_perm[MOE_MAX_ASSIGN];         // steps below; the plan gets a copy
     __shared__ int32_t s_nact, s_nmiss;
     const int n = T * k;
     const bool only_listed = (flags & MOE_VERIFY_ONLY_LISTED) != 0;
@@ -214,7 +216,9 @@ __device__ inline void plan_body(Plan *__restrict__ plan, int T, int E, int k, i
         }
     }
     __syncthreads();
-    histogram_perm(s_ids, n, E, plan->count, plan->off, plan->perm, s_count);
+    histogram_perm(s_ids, n, E, plan->count, s_off, s_perm, s_count);
+    for (int e = threadIdx.x; e <= E; e += blockDim.x) plan->off[e] = s_off[e];
+    for (int i = threadIdx.x; i < n; i += blockDim.x) plan->perm[i] = s_perm[i];
 
     // shared experts: active slots [0, S), rows T*k + s*T + t
     for (int i = threadIdx.x; i < S * T; i += blockDim.x) {
@@ -244,7 +248,7 @@ __device__ inline void plan_body(Plan *__restrict__ plan, int T, int E, int k, i
                 int u = nact + __popcll(bp & below);
                 int slot = s_slot[e];
                 plan->act_expert[u] = e;
-                plan->act_off[u] = plan->off[e];
+                plan->act_off[u] = s_off[e];
                 plan->act_cnt[u] = s_count[e];
                 plan->act_w0[u] = (uint64_t)(w0 + (size_t)slot * stride0);
                 plan->act_w1[u] = w1 ? (uint64_t)(w1 + (size_t)slot * stride1) : 0;
@@ -257,7 +261,7 @@ __device__ inline void plan_body(Plan *__restrict__ plan, int T, int E, int k, i
     }
     __syncthreads();
     for (int pos = threadIdx.x; pos < n; pos += blockDim.x) {
-        int a = plan->perm[pos];
+        int a = s_perm[pos];
         int e = s_ids[a];
         plan->row_tok[pos] = a / k;
         plan->row_w[pos] = get<kAgent>(&plan->w[a]);
