@@ -169,3 +169,46 @@ def test_library_rejects_bad_arguments():
         c.plan(elb, 7)
     with pytest.raises(B.MoeError):
         S.Cache(1, 8, 9)
+
+
+def test_coverage_ordering_on_a_routed_stream():
+    """The experiment of the paper's hit-rate table in small: expert ids of an AR(1) token stream
+    from the oracle router, one token per step, K drafted tokens per cycle known ahead.  Looking
+    ahead covers more than recency alone; the library reproduces the oracle's counts."""
+    import numpy as np
+    import synth
+    from oracle import oracle as orc
+    cfg = synth.config_by_name("tiny")
+    L, N, K, k, E = 3, 160, 3, cfg.top_k, cfg.n_experts
+    ids = []
+    for li in range(L):
+        x = synth.make_tokens(cfg, N, layer=li, kind="ar1")
+        r = orc.route(orc.bits(x), orc.bits(synth.make_router(cfg, li)), None, k, True)
+        ids.append(np.asarray(r[0]))
+    ids = np.stack(ids)                                            # [L, N, k]
+
+    def play(make_cache, make_window, plan, predicted):
+        c = make_cache(L, E, 3)
+        pos = 0
+        while pos + K + 1 <= N:
+            for row in range(K + 1):
+                if row in predicted:
+                    w = make_window([[[(int(e), 1.0) for e in ids[li, pos + row]] for li in range(L)]])
+                    plan(c, w)
+                for li in range(L):
+                    need = [int(e) for e in ids[li, pos + row]]
+                    c.use(li, need)
+                    t = c.slot_table(li)
+                    c.on_demand(li, sorted({e for e in need if t[e] < 0}))
+                c.end_window()
+            pos += K + 1
+        return c
+
+    cover = {}
+    for name, predicted in (("lru", []), ("single", [0]), ("speculative", list(range(K)))):
+        o = play(SO.Cache, lambda w: w, lambda c, w: c.plan(w, 3), predicted)
+        lib = play(S.Cache, elb_from, lambda c, w: (c.plan(w, S.PHASE_SATURATE), w.close()), predicted)
+        assert lib.stats() == (o.hits, o.misses)
+        cover[name] = o.hits / (o.hits + o.misses)
+    assert cover["lru"] < cover["single"] < cover["speculative"]
+    assert cover["speculative"] >= K / (K + 1)                     # every predicted token's experts were in place
