@@ -35,11 +35,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(cfg, T, mean_u):
+def algorithmic_bytes(cfg, T, mean_u, symmetric=False):
     """Bytes the method has to move per call (selected experts' weights once + small operands)."""
     H, E, I, k, S, g = cfg.hidden, cfg.n_experts, cfg.inter, cfg.top_k, cfg.n_shared, cfg.group_size
     P = 3 * H * I
-    int4_expert = P // 2 + (P // g) * 4
+    int4_expert = P // 2 + (P // g) * (2 if symmetric else 4)      # codes + fp16 scale (+ fp16 zero)
     return {
         "draft_call": k * int4_expert + S * 2 * P + E * H * 2 + H * 2 + H * 4,              # one token
         "verify_call": mean_u * 2 * P + S * 2 * P + E * H * 2 + T * H * 4,
@@ -152,10 +152,11 @@ def resident_leg(args, cfg, ctx, dev):
     # ---- layers: layer 0 from the CPU streams (the oracle can see it), the rest drawn on the GPU
     t0 = time.time()
     layers, xs = [], []
-    L0 = synth.make_layer(cfg, 0, quant_device=dev)
+    sym = args.int4 == "symmetric"
+    L0 = synth.make_layer(cfg, 0, quant_device=dev, symmetric=sym)
     for li in range(n_layers):
-        L = L0 if li == 0 else synth.make_layer(cfg, li, device=dev)
-        layers.append(DeviceLayer(ctx, cfg, L, max_tokens=T))
+        L = L0 if li == 0 else synth.make_layer(cfg, li, device=dev, symmetric=sym)
+        layers.append(DeviceLayer(ctx, cfg, L, max_tokens=T, symmetric=sym))
         xs.append(synth.make_tokens(cfg, T, layer=li).to(dev))
         if li:
             del L
@@ -228,10 +229,12 @@ def resident_leg(args, cfg, ctx, dev):
     uniq = [len(set(bufs[li]["idv"].cpu().numpy().reshape(-1).tolist())) for li in range(n_layers)]
     mean_u = float(np.mean(uniq))
     mean_u_run = float(np.mean([uniq[(args.warmup + i) % n_layers] for i in range(args.steps)]))
-    nbytes = algorithmic_bytes(cfg, T, mean_u_run)
+    nbytes = algorithmic_bytes(cfg, T, mean_u_run, sym)
 
     # ---- per-kernel time (eager, event pairs around every kernel launch)
     roofline, extra = None, {}
+    if sym:
+        extra["int4_format"] = "symmetric (z = 8, scale blobs)"
     if args.mode == "graph":
         extra["ms_graph"] = round(ms_graph, 4)
     if not args.no_profile:
@@ -548,6 +551,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="distinct layers to rotate over (0 = config default)")
     ap.add_argument("--mode", default="graph", choices=["graph", "eager"],
                     help="how the timed steps are launched (per-kernel timing always runs eagerly)")
+    ap.add_argument("--int4", default="asymmetric", choices=["asymmetric", "symmetric"],
+                    help="draft weight format: scale + zero per group (default) or scales only with z = 8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--slots", type=int, default=0,

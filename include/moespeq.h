@@ -59,6 +59,14 @@
  *    down part, after the (I / 32) * (H / g) * 64 gate/up entries: entry
  *      ((group * (H / 64) + rt) * 16 + r) * 4 + d, group = input column / g.
  *    moe_int4_expert_sz_bytes() = 3 H I / g * 4 bytes.
+ *  scale blob of the symmetric format (z = 8 for every group, the usual signed 4-bit weight
+ *  q - 8; moe_int4_experts.symmetric != 0): 2-byte entries (fp16 s), no zeros.  Two groups
+ *  (gate/up) or two row tiles (down) share one 16-byte unit per r, which holds the four
+ *  entries d = 0..3 of the even one and then those of the odd one:
+ *    gate/up part: entry (((slice * (H / g / 2) + group / 2) * 16 + r) * 2 + group % 2) * 4 + d;
+ *    down part, after the (I / 32) * (H / g) * 64 gate/up entries: entry
+ *      ((((group * (H / 128)) + rt / 2) * 16 + r) * 2 + rt % 2) * 4 + d.
+ *    moe_int4_expert_scale_bytes() = 3 H I / g * 2 bytes.  Needs H / g even and H % 128 == 0.
  */
 #ifndef MOESPEQ_H
 #define MOESPEQ_H
@@ -107,6 +115,7 @@ typedef struct moe_int4_experts {
     const void *sz;
     size_t expert_stride_q;
     size_t expert_stride_sz;
+    int32_t symmetric;     /* nonzero: sz holds scale blobs of the symmetric format, z = 8 */
 } moe_int4_experts;
 
 /* ---- context and helpers (host only) ------------------------------------------------- */
@@ -129,6 +138,8 @@ int moe_validate_desc(const moe_layer_desc *desc);
 size_t moe_bf16_expert_bytes(const moe_layer_desc *desc);
 size_t moe_int4_expert_q_bytes(const moe_layer_desc *desc);
 size_t moe_int4_expert_sz_bytes(const moe_layer_desc *desc);
+/* scale blob of the symmetric format; 0 also when the shape does not allow that format */
+size_t moe_int4_expert_scale_bytes(const moe_layer_desc *desc);
 
 /* Bytes of device workspace that moe_draft_layer_int4 / moe_verify_layer_bf16 need for up to
  * `max_tokens` tokens per call (256-byte aligned base). */

@@ -19,7 +19,7 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_MISSING_EXP
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_status_string", "moe_last_hip_error", "moe_validate_desc",
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
-    "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
+    "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
     "moe_profile_enable", "moe_profile_read", "moe_kernel_name", "moe_stream_read_probe",
 ]
@@ -53,7 +53,8 @@ class LayerDesc(ctypes.Structure):
 
 class Int4Experts(ctypes.Structure):
     _fields_ = [("q", ctypes.c_void_p), ("sz", ctypes.c_void_p),
-                ("expert_stride_q", ctypes.c_size_t), ("expert_stride_sz", ctypes.c_size_t)]
+                ("expert_stride_q", ctypes.c_size_t), ("expert_stride_sz", ctypes.c_size_t),
+                ("symmetric", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -75,7 +76,8 @@ def load_library():
         L.moe_status_string.argtypes = [i32]; L.moe_status_string.restype = ctypes.c_char_p
         L.moe_last_hip_error.argtypes = [vp]; L.moe_last_hip_error.restype = ctypes.c_char_p
         L.moe_validate_desc.argtypes = [dp]
-        for n in ("moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes"):
+        for n in ("moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
+                  "moe_int4_expert_scale_bytes"):
             getattr(L, n).argtypes = [dp]; getattr(L, n).restype = sz
         L.moe_workspace_bytes.argtypes = [dp, i32, ctypes.POINTER(sz)]
         L.moe_workspace_init.argtypes = [vp, vp, sz, vp]
@@ -93,7 +95,8 @@ def load_library():
         L.moe_stream_read_probe.argtypes = [vp, vp, ctypes.c_size_t, i32, vp, vp]
         for n in EXPORTS:
             if n not in ("moe_status_string", "moe_last_hip_error", "moe_bf16_expert_bytes",
-                         "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes", "moe_kernel_name"):
+                         "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
+                         "moe_int4_expert_scale_bytes", "moe_kernel_name"):
                 getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -117,6 +120,10 @@ def int4_expert_q_bytes(desc: LayerDesc) -> int:
 
 def int4_expert_sz_bytes(desc: LayerDesc) -> int:
     return load_library().moe_int4_expert_sz_bytes(ctypes.byref(desc))
+
+
+def int4_expert_scale_bytes(desc: LayerDesc) -> int:
+    return load_library().moe_int4_expert_scale_bytes(ctypes.byref(desc))
 
 
 def workspace_bytes(desc: LayerDesc, max_tokens: int) -> int:
@@ -180,8 +187,9 @@ class Context:
                                              _stream(stream)), "moe_route_topk")
 
     def draft_layer_int4(self, desc, x, w_router, router_bias, q_blob, sz_blob, stride_q, stride_sz,
-                         shared_bf16, T, y_f32, ids_out, conf_out, workspace, stream=None):
-        ex = Int4Experts(q_blob.data_ptr(), sz_blob.data_ptr(), stride_q, stride_sz)
+                         shared_bf16, T, y_f32, ids_out, conf_out, workspace, stream=None,
+                         symmetric=False):
+        ex = Int4Experts(q_blob.data_ptr(), sz_blob.data_ptr(), stride_q, stride_sz, int(bool(symmetric)))
         self._check(self._lib.moe_draft_layer_int4(
             self._h, ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), ctypes.byref(ex),
             _ptr(shared_bf16), T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _ptr(workspace),

@@ -224,6 +224,14 @@ size_t moe_int4_expert_sz_bytes(const moe_layer_desc *d)
     return (size_t)3 * d->hidden * d->inter / d->group_size * 4;
 }
 
+size_t moe_int4_expert_scale_bytes(const moe_layer_desc *d)
+{
+    if (check_desc(d) != MOE_OK) return 0;
+    // two groups (gate/up) and two row tiles (down) share a 16-byte unit
+    if ((d->hidden / d->group_size) % 2 || d->hidden % 128) return 0;
+    return (size_t)3 * d->hidden * d->inter / d->group_size * 2;
+}
+
 int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *bytes)
 {
     if (!bytes || check_desc(desc) != MOE_OK) return MOE_ERR_INVALID_ARG;
@@ -274,8 +282,9 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         !aligned(routed->sz, 16) || routed->expert_stride_q % 16 || routed->expert_stride_sz % 16 ||
         !aligned(y, 16) || !aligned(ids_out, 4) || !aligned(conf_out, 4) || !aligned(shared, 16))
         return MOE_ERR_INVALID_ARG;
-    if (routed->expert_stride_q < moe_int4_expert_q_bytes(desc) ||
-        routed->expert_stride_sz < moe_int4_expert_sz_bytes(desc))
+    const size_t sz_bytes = routed->symmetric ? moe_int4_expert_scale_bytes(desc) : moe_int4_expert_sz_bytes(desc);
+    if (sz_bytes == 0 || routed->expert_stride_q < moe_int4_expert_q_bytes(desc) ||
+        routed->expert_stride_sz < sz_bytes)
         return MOE_ERR_INVALID_ARG;
     if (desc->n_shared > 0 && !shared) return MOE_ERR_INVALID_ARG;
     const WsLayout L = ws_layout(*desc, T);
@@ -289,6 +298,7 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     a.x = x; a.wr = wr; a.bias = bias;
     a.q = routed->q; a.sz = routed->sz;
     a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
+    a.symmetric = routed->symmetric ? 1 : 0;
     a.slots = (unsigned long long *)(ws + L.slots);
     a.replica_stride = L.slot_replica_bytes / 8;
     a.tickets = (uint32_t *)(ws + L.tickets);

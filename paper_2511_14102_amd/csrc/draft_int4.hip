@@ -125,8 +125,32 @@ struct FusedArgs {
     int T, H, E, I, k, g, S, renorm;
 };
 
-// MT: token capacity of the launch (1, 2, 4 or 8); UPG: 32-code units per group (g / 32).
-template <int MT, int UPG>
+// Scale and zero of the four row blocks d of one (group, lane row): the asymmetric format keeps
+// a 4-byte {s, z} entry per d, the symmetric one (z = 8) only the four fp16 scales.
+template <bool SYM> struct GroupParams;
+template <> struct GroupParams<false> {
+    uint32_t w[4];
+    __device__ float scale(int d) const {
+        const uint32_t e = d == 0 ? w[0] : (d == 1 ? w[1] : (d == 2 ? w[2] : w[3]));
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(e & 0xffff));
+    }
+    __device__ float zero128(int d) const {                   // z + 128
+        const uint32_t e = d == 0 ? w[0] : (d == 1 ? w[1] : (d == 2 ? w[2] : w[3]));
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(e >> 16)) + 128.f;
+    }
+};
+template <> struct GroupParams<true> {
+    uint32_t w[2];
+    __device__ float scale(int d) const {
+        const uint32_t e = (d >> 1) ? w[1] : w[0];
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)((d & 1) ? e >> 16 : e & 0xffff));
+    }
+    __device__ float zero128(int) const { return 136.f; }
+};
+
+// MT: token capacity of the launch (1, 2, 4 or 8); UPG: 32-code units per group (g / 32); SYM:
+// symmetric format (scale blobs, z = 8).
+template <int MT, int UPG, bool SYM>
 __global__ __launch_bounds__(kThreads, MT <= 2 ? 4 : 2)   // MT <= 2: 4 waves per SIMD, two workgroups per CU
 void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 {
@@ -368,9 +392,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                           (size_t)slice * (H / 64) * 64 + lane;
         // scale/zero: 16 B = the 4 row blocks' (s, z) of lane row r; [gate|up (slice, group)] then
         // [down (group of I, rt)]
-        const u32x4 *szgu = reinterpret_cast<const u32x4 *>(szb) + (size_t)slice * G * 16 + r;
-        const u32x4 *szd = reinterpret_cast<const u32x4 *>(szb) + (size_t)nslice * G * 16 +
-                           (size_t)((slice * 32) / g) * (H / 64) * 16 + r;
+        // (symmetric format: 16 B = the 4 row blocks' s of row r for two groups / two row tiles)
+        constexpr int kEpl = SYM ? 2 : 1;                        // groups (row tiles) per 16-byte load
+        const u32x4 *szgu = reinterpret_cast<const u32x4 *>(szb) + (size_t)slice * (G / kEpl) * 16 + r;
+        const u32x4 *szd = reinterpret_cast<const u32x4 *>(szb) + (size_t)nslice * (G / kEpl) * 16 +
+                           (size_t)((slice * 32) / g) * (H / (64 * kEpl)) * 16 + r;
 
         // A-operand row of this lane: token slot r (slots >= cnt repeat slot 0; their D rows are ignored)
         const int my_tok = s_row_a[r < cnt ? r : 0] / k;
@@ -393,10 +419,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         // last tile.  The compiler counts the loads in flight in program order; a load under a
         // branch makes it wait for all of them wherever it needs one, which empties the window.
         const int nrt = H / 64;
-        const int u0 = ((wave * G) / kWaves) * UPG, u1 = (((wave + 1) * G) / kWaves) * UPG;
+        // (the symmetric format shares a load between two groups / row tiles: whole pairs per wave)
+        const int u0 = ((wave * (G / kEpl)) / kWaves) * kEpl * UPG, u1 = (((wave + 1) * (G / kEpl)) / kWaves) * kEpl * UPG;
         const int nt = u1 - u0;
         const int ntp = (nt + kGuWin - 1) / kGuWin * kGuWin;
-        const int r0 = (wave * nrt) / kWaves, r1 = ((wave + 1) * nrt) / kWaves;   // this wave's down row tiles
+        const int r0 = ((wave * (nrt / kEpl)) / kWaves) * kEpl, r1 = (((wave + 1) * (nrt / kEpl)) / kWaves) * kEpl;   // this wave's down row tiles
         const int rt_last = r1 > r0 ? r1 - 1 : 0;
         const int g_last = nt > 0 ? (u1 - 1) / UPG : 0;
         auto stream_ptr = [&](int p) -> const u32x4 * {            // p: position in the stream
@@ -406,18 +433,32 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             const u32x4 *dp = qd + (size_t)(rt < r1 ? rt : rt_last) * 64;
             return p < ntp ? gp : dp;
         };
-        // Scale/zero entries are fetched four groups (or four row tiles) per load: lane group c
-        // takes the 16 bytes of row r of group first + 4 pk + c, and a lane picks the entry of
-        // the group at hand from that lane group with a lane permute.
-        constexpr int kSzPacks = (kSzWin + 3) / 4;
+        // Scale/zero entries are fetched 4 kEpl groups (or row tiles) per load: lane group c
+        // takes the 16 bytes of row r of load unit first / kEpl + 4 pk + c, and a lane picks the
+        // entry of the group at hand from that lane group with a lane permute.  `first` is a
+        // multiple of kEpl everywhere below.
+        constexpr int kPerPack = 4 * kEpl;
+        constexpr int kSzPacks = (kSzWin + kPerPack - 1) / kPerPack;
         auto gsz_ptr = [&](int first, int pk) {
-            const int gi = first + 4 * pk + c;
-            return szgu + (size_t)(gi < g_last ? gi : g_last) * 16;
+            const int gi = first / kEpl + 4 * pk + c;
+            const int last = g_last / kEpl;
+            return szgu + (size_t)(gi < last ? gi : last) * 16;
         };
-        auto pick = [&](const u32x4 &v, int from) {               // the entry held by lane group `from`, row r
-            const int src = from * 16 + r;
-            return (u32x4){(uint32_t)__shfl((int)v.x, src, 64), (uint32_t)__shfl((int)v.y, src, 64),
-                           (uint32_t)__shfl((int)v.z, src, 64), (uint32_t)__shfl((int)v.w, src, 64)};
+        // parameters of the j-th group (row tile) after the packs' first one, lane row r
+        auto pick = [&](const u32x4 *packs, int j) {
+            const u32x4 &v = packs[j / kPerPack];
+            const int src = ((j / kEpl) % 4) * 16 + r;
+            GroupParams<SYM> p;
+            if constexpr (SYM) {
+                p.w[0] = (uint32_t)__shfl((int)((j & 1) ? v.z : v.x), src, 64);
+                p.w[1] = (uint32_t)__shfl((int)((j & 1) ? v.w : v.y), src, 64);
+            } else {
+                p.w[0] = (uint32_t)__shfl((int)v.x, src, 64);
+                p.w[1] = (uint32_t)__shfl((int)v.y, src, 64);
+                p.w[2] = (uint32_t)__shfl((int)v.z, src, 64);
+                p.w[3] = (uint32_t)__shfl((int)v.w, src, 64);
+            }
+            return p;
         };
         float tot[4][NI];
         f32x4 acc[4];
@@ -453,15 +494,13 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     xa = xn;
                     if (i % UPG == UPG - 1) {                 // end of a group: scale / zero / offset
                         const int gi = ku / UPG;
-                        const u32x4 szv = pick(gsz[(i / UPG) / 4], (i / UPG) % 4);
-                        const uint32_t sw[4] = {szv.x, szv.y, szv.z, szv.w};
+                        const GroupParams<SYM> gp = pick(gsz, i / UPG);
                         float xs[NI];
 #pragma unroll
                         for (int j = 0; j < NI; ++j) xs[j] = s_xsum[tok[j] * G + gi];
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
-                            const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] & 0xffff));
-                            const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(sw[d] >> 16)) + 128.f;
+                            const float sc = gp.scale(d), zp = gp.zero128(d);
 #pragma unroll
                             for (int j = 0; j < NI; ++j) tot[d][j] += sc * (acc[d][j] - zp * xs[j]);
                             acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -473,10 +512,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = gsz_next[pk];
         }
         // the window now holds this wave's first kGuWin down tiles; their scales follow
-        constexpr int kDPacks = (kGuWin + 3) / 4;
+        constexpr int kDPacks = (kGuWin + kPerPack - 1) / kPerPack;
         auto dsz_ptr = [&](int first, int pk) {
-            const int rt = first + 4 * pk + c;
-            return szd + (size_t)(rt < r1 ? rt : rt_last) * 16;
+            const int rt = first / kEpl + 4 * pk + c;
+            const int last = rt_last / kEpl;
+            return szd + (size_t)(rt < last ? rt : last) * 16;
         };
         u32x4 dsz[kDPacks];
 #pragma unroll
@@ -566,17 +606,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     win[i] = __builtin_nontemporal_load(qd + (size_t)(rtn < r1 ? rtn : rt_last) * 64);
                 }
                 if (rt < r1) {
-                    const u32x4 szv = pick(dsz[i / 4], i % 4);
-                    const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w}, sw[4] = {szv.x, szv.y, szv.z, szv.w};
+                    const GroupParams<SYM> gp = pick(dsz, i);
+                    const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
                     for (int q = 0; q < 4 / kBpa; ++q) {
                         f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int bl = 0; bl < kBpa; ++bl) o = mfma(hab[bl], unpack8(qw[q * kBpa + bl], uk), o);
                         const int d = q * kBpa + my_bl;          // this lane's row block of the tile
-                        const uint32_t swd = d == 0 ? sw[0] : (d == 1 ? sw[1] : (d == 2 ? sw[2] : sw[3]));
-                        const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(swd & 0xffff));
-                        const float zp = (float)__builtin_bit_cast(_Float16, (uint16_t)(swd >> 16)) + 128.f;
+                        const float sc = gp.scale(d), zp = gp.zero128(d);
 #pragma unroll
                         for (int j = 0; j < ND; ++j) {
                             if (live[j]) {
@@ -700,16 +738,25 @@ void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st
     launch(kernel, grid, block, lds, st, x, a);
 }
 
-template <int MT>
+template <int MT, bool SYM>
 void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st)
 {
     const int maxu = a.E < a.T * a.k ? a.E : a.T * a.k;
     const dim3 grid(maxu * (a.I / 32)), block(kThreads);
     // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums
     const size_t lds = (size_t)MT * (a.H + 8) * 2 + (size_t)MT * (a.H / a.g) * 4;
-    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1>, grid, block, lds, st, x, a);
-    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2>, grid, block, lds, st, x, a);
-    else launch_with_lds(draft_fused_kernel<MT, 4>, grid, block, lds, st, x, a);
+    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM>, grid, block, lds, st, x, a);
+    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM>, grid, block, lds, st, x, a);
+    else launch_with_lds(draft_fused_kernel<MT, 4, SYM>, grid, block, lds, st, x, a);
+}
+
+template <bool SYM>
+void launch_fused(int T, const uint16_t *x, const FusedArgs &a, hipStream_t st)
+{
+    if (T <= 1) launch_fused_t<1, SYM>(x, a, st);
+    else if (T <= 2) launch_fused_t<2, SYM>(x, a, st);
+    else if (T <= 4) launch_fused_t<4, SYM>(x, a, st);
+    else launch_fused_t<8, SYM>(x, a, st);
 }
 
 }  // namespace
@@ -724,10 +771,8 @@ void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
     a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;
-    if (s.T <= 1) launch_fused_t<1>(x, a, st);
-    else if (s.T <= 2) launch_fused_t<2>(x, a, st);
-    else if (s.T <= 4) launch_fused_t<4>(x, a, st);
-    else launch_fused_t<8>(x, a, st);
+    if (d.symmetric) launch_fused<true>(s.T, x, a, st);
+    else launch_fused<false>(s.T, x, a, st);
 }
 
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st)

@@ -99,6 +99,7 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
 struct DraftFusedArgs {
     const void *x, *wr; const float *bias;
     const void *q, *sz; size_t stride_q, stride_sz;
+    int symmetric;                     // sz holds scale blobs (z = 8)
     unsigned long long *slots; size_t replica_stride; uint32_t *tickets;
     float *y; int32_t *ids_out; float *conf_out;
     Plan *plan; const void *shared; size_t shared_stride;

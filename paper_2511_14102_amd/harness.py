@@ -16,11 +16,14 @@ class DeviceLayer:
     L: a layer in the logical layouts (see synth.gen): 'router', 'router_bias', 'gate', 'up',
     'down' (bf16, E+S experts) and, when the draft path is wanted, 'q_*', 's_*', 'z_*'.
     resident: expert ids that get a slot (default: all E, expert e in slot e); others are absent
-    until load_expert() is called.  n_slots: size of the slot pool (default len(resident))."""
+    until load_expert() is called.  n_slots: size of the slot pool (default len(resident)).
+    symmetric: the int4 experts go to the device in the symmetric format (scale blobs); every
+    zero point of L must then be 8."""
 
     def __init__(self, ctx: B.Context, cfg, L: Dict, max_tokens: int,
                  resident: Optional[Sequence[int]] = None, n_slots: Optional[int] = None,
-                 draft: bool = True, verify: bool = True, device: str = "cuda:0"):
+                 draft: bool = True, verify: bool = True, device: str = "cuda:0",
+                 symmetric: bool = False):
         self.ctx, self.cfg, self.dev = ctx, cfg, torch.device(device)
         self.desc = B.LayerDesc.from_config(cfg)
         assert B.validate_desc(self.desc) == 0, "unsupported layer shape"
@@ -30,7 +33,9 @@ class DeviceLayer:
         self.bias = None if L.get("router_bias") is None else L["router_bias"].to(dev).contiguous()
         self.bf16_bytes = B.bf16_expert_bytes(self.desc)
         self.q_bytes = B.int4_expert_q_bytes(self.desc)
-        self.sz_bytes = B.int4_expert_sz_bytes(self.desc)
+        self.symmetric = bool(symmetric)
+        self.sz_bytes = B.int4_expert_scale_bytes(self.desc) if symmetric else B.int4_expert_sz_bytes(self.desc)
+        assert self.sz_bytes > 0, "shape not supported by the symmetric format"
         self.workspace = torch.empty(B.workspace_bytes(self.desc, max_tokens), dtype=torch.uint8, device=dev)
         ctx.workspace_init(self.workspace)
         self.max_tokens = max_tokens
@@ -45,10 +50,12 @@ class DeviceLayer:
             self.q_blob = torch.empty(E * self.q_bytes, dtype=torch.uint8, device=dev)
             self.sz_blob = torch.empty(E * self.sz_bytes, dtype=torch.uint8, device=dev)
             for e in range(E):
-                qb, sb = pack.pack_int4_expert(
-                    {n: L["q_" + n][e].to(dev) for n in ("gate", "up", "down")},
-                    {n: L["s_" + n][e].to(dev) for n in ("gate", "up", "down")},
-                    {n: L["z_" + n][e].to(dev) for n in ("gate", "up", "down")})
+                q, s, z = ({n: L[p + n][e].to(dev) for n in ("gate", "up", "down")} for p in ("q_", "s_", "z_"))
+                if symmetric:
+                    assert all(bool((v == 8).all()) for v in z.values()), "symmetric format needs z = 8"
+                    qb, sb = pack.pack_int4_expert_symmetric(q, s)
+                else:
+                    qb, sb = pack.pack_int4_expert(q, s, z)
                 self.q_blob[e * self.q_bytes:(e + 1) * self.q_bytes] = qb
                 self.sz_blob[e * self.sz_bytes:(e + 1) * self.sz_bytes] = sb
         self.slot_pool = self.slot_of_expert = None
@@ -101,7 +108,7 @@ class DeviceLayer:
         conf = torch.empty((T, k), dtype=torch.float32, device=dev) if conf is None else conf
         self.ctx.draft_layer_int4(self.desc, x, self.router, self.bias, self.q_blob, self.sz_blob,
                                   self.q_bytes, self.sz_bytes, self.shared, T, y, ids, conf,
-                                  self.workspace, stream)
+                                  self.workspace, stream, symmetric=self.symmetric)
         return dict(y=y, ids=ids, conf=conf)
 
     def verify(self, x: torch.Tensor, flags: int = 0, y=None, ids=None, stream=None):

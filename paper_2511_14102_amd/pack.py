@@ -1,5 +1,6 @@
 """Packers from row-major logical arrays to the kernel-native weight layouts documented in
-include/moespeq.h ("tile16x32" for bf16, slice tiles for the int4 codes and scale/zero).
+include/moespeq.h ("tile16x32" for bf16, slice tiles for the int4 codes and scale/zero, or scales alone in the
+symmetric format).
 
 Off the hot path: run once when weights are loaded.  Works on CPU or GPU torch tensors and
 returns flat uint8 tensors (byte images of the blobs)."""
@@ -83,6 +84,32 @@ def pack_int4_down_sz(sd, zd) -> torch.Tensor:
     H, G = sd.shape
     t = _sz_pairs(sd, zd).reshape(H // 64, 4, 16, G, 2)              # [rt, d, r, group, 2]
     return t.permute(3, 0, 2, 1, 4).contiguous().view(torch.uint8).reshape(-1)
+
+
+def pack_int4_gateup_scales(sg, su) -> torch.Tensor:
+    """Symmetric format: scales [I, H/g] of gate and up -> fp16 entries (slice, group pair, r,
+    group parity, d), d as for the codes."""
+    I, G = sg.shape
+    assert sg.dtype == torch.float16 and su.dtype == torch.float16 and G % 2 == 0
+    t = torch.cat([sg.reshape(I // 32, 2, 16, G // 2, 2), su.reshape(I // 32, 2, 16, G // 2, 2)], dim=1)
+    return t.permute(0, 3, 2, 4, 1).contiguous().view(torch.uint8).reshape(-1)   # [slice, pair, r, parity, d]
+
+
+def pack_int4_down_scales(sd) -> torch.Tensor:
+    """Symmetric format: scales [H, I/g] of down -> fp16 entries (group, row-tile pair, r, row-tile
+    parity, d)."""
+    H, G = sd.shape
+    assert sd.dtype == torch.float16 and H % 128 == 0
+    t = sd.reshape(H // 128, 2, 4, 16, G)                             # [rt pair, parity, d, r, group]
+    return t.permute(4, 0, 3, 1, 2).contiguous().view(torch.uint8).reshape(-1)
+
+
+def pack_int4_expert_symmetric(q, s):
+    """q, s: dicts gate/up/down of one expert whose zero points are all 8 -> (codes blob,
+    scale blob)."""
+    qb = torch.cat([pack_int4_gateup_codes(q["gate"], q["up"]), pack_int4_down_codes(q["down"])])
+    sb = torch.cat([pack_int4_gateup_scales(s["gate"], s["up"]), pack_int4_down_scales(s["down"])])
+    return qb, sb
 
 
 def pack_int4_expert(q, s, z):

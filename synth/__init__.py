@@ -12,6 +12,7 @@ from .gen import (
     make_router,
     make_experts_bf16,
     quantize_rtn_int4,
+    quantize_rtn_int4_symmetric,
     make_tokens,
     make_layer,
     zipf_bias,
@@ -21,6 +22,7 @@ from .gen import (
 
 __all__ = [
     "LayerConfig", "CONFIGS", "config_by_name",
-    "make_router", "make_experts_bf16", "quantize_rtn_int4", "make_tokens", "make_layer",
+    "make_router", "make_experts_bf16", "quantize_rtn_int4",
+    "quantize_rtn_int4_symmetric", "make_tokens", "make_layer",
     "zipf_bias", "skew_bias", "layer_seed",
 ]

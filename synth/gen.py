@@ -98,6 +98,27 @@ def quantize_rtn_int4(w: torch.Tensor, group_size: int):
     return (q.to(torch.uint8).reshape(*lead, K), s16, z.to(torch.float16))
 
 
+def quantize_rtn_int4_symmetric(w: torch.Tensor, group_size: int):
+    """Round-to-nearest symmetric int4 (signed 4-bit weights -8..7 stored as codes 0..15 with
+    zero point 8) over groups of `group_size` input columns.
+
+    scale = fp16(max|w| / 7) over the group; a group whose scale rounds to 0 gets scale 1 and
+    all codes 8.  code = clamp(rint(w / scale), -8, 7) + 8 with the fp16-rounded scale, in fp64,
+    rint = round-half-to-even.  Returns (codes uint8, scale fp16, zero fp16 == 8 everywhere), the
+    same triple as the asymmetric quantiser.
+    """
+    *lead, K = w.shape
+    assert K % group_size == 0
+    wg = w.to(torch.float64).reshape(*lead, K // group_size, group_size)
+    s16 = (wg.abs().amax(-1) / 7.0).to(torch.float16)
+    dead = s16 == 0
+    s16 = torch.where(dead, torch.ones_like(s16), s16)
+    s = s16.to(torch.float64)
+    q = torch.clamp(torch.round(wg / s.unsqueeze(-1)), -8, 7) + 8
+    q = torch.where(dead.unsqueeze(-1), torch.full_like(q, 8), q)
+    return (q.to(torch.uint8).reshape(*lead, K), s16, torch.full_like(s16, 8.0))
+
+
 def zipf_bias(cfg: LayerConfig, layer: int = 0) -> torch.Tensor:
     """Router-logit bias ln(pi_e) with pi_e proportional to rank(e)^-1.1 under a seeded
     random ranking of the experts."""
@@ -137,7 +158,7 @@ def make_tokens(cfg: LayerConfig, T: int, layer: int = 0, step: int = 0,
 
 def make_layer(cfg: LayerConfig, layer: int = 0, bias: Optional[str] = None,
                quantize: bool = True, device: str = "cpu",
-               quant_device: Optional[str] = None) -> Dict[str, object]:
+               quant_device: Optional[str] = None, symmetric: bool = False) -> Dict[str, object]:
     """One full layer in the logical layouts listed in the module docstring.
 
     bias: None -> what cfg.router asks for ('zipf' -> zipf_bias, otherwise no bias);
@@ -147,6 +168,7 @@ def make_layer(cfg: LayerConfig, layer: int = 0, bias: Optional[str] = None,
             layer_seed (benchmark filler layers; router and bias are still the CPU ones).
     quant_device: where the RTN quantiser runs (same fp64 elementwise arithmetic, so the same
             result); results are returned on `device`.
+    symmetric: quantise with quantize_rtn_int4_symmetric (every zero point is 8).
     """
     E = cfg.n_experts
     L: Dict[str, object] = {"cfg": cfg, "layer": layer}
@@ -166,9 +188,11 @@ def make_layer(cfg: LayerConfig, layer: int = 0, bias: Optional[str] = None,
         for name in ("gate", "up", "down"):
             qs, ss, zs = [], [], []
             for e in range(E):          # one expert at a time bounds the fp64 temporaries
-                q, s, z = quantize_rtn_int4(w[name][e].to(qdev), cfg.group_size)
+                quant = quantize_rtn_int4_symmetric if symmetric else quantize_rtn_int4
+                q, s, z = quant(w[name][e].to(qdev), cfg.group_size)
                 qs.append(q.to(device)); ss.append(s.to(device)); zs.append(z.to(device))
             L["q_" + name] = torch.stack(qs)
             L["s_" + name] = torch.stack(ss)
             L["z_" + name] = torch.stack(zs)
+        L["symmetric"] = symmetric
     return L

@@ -107,6 +107,48 @@ def test_draft_layer(case):
     assert rel_err(to_np(r2["y"]), to_np(r["y"])) <= 1e-5
 
 
+@pytest.mark.parametrize("name", ["tiny", "phi", "qwen3", "dsv2lite"])
+def test_draft_layer_symmetric_format(ctx, name):
+    # z = 8 in every group, scale blobs on the device (group sizes 32, 128, 64, 128; the last
+    # with shared experts); the oracle sees the same codes and scales with an explicit z = 8
+    cfg = synth.config_by_name(name)
+    say("building", cfg.name, "symmetric int4")
+    qdev = "cuda:0"
+    L = synth.make_layer(cfg, 0, quant_device=qdev, symmetric=True)
+    A = oracle_arrays(L)
+    D = DeviceLayer(ctx, cfg, L, max_tokens=8, verify=False, symmetric=True)
+    D2 = DeviceLayer(ctx, cfg, L, max_tokens=8, verify=False) if name in ("tiny", "qwen3") else None
+    torch.cuda.synchronize()
+    T = min(max(cfg.verify_tokens), 8)
+    x = tokens_with_clear_routing(cfg, A, T, step=20)
+    ref = oracle_draft(A, x)
+    for t in range(min(T, 3)):
+        say("draft (symmetric)", cfg.name, "token", t)
+        r = D.draft(x[t:t + 1].cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"][t:t + 1])
+        e = rel_err(to_np(r["y"]), ref["y"][t:t + 1])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_DRAFT
+    for Tm in sorted({2, min(T, 4), T}):
+        say("draft (symmetric)", cfg.name, "T", Tm, "in one call")
+        r = D.draft(x[:Tm].cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"][:Tm])
+        np.testing.assert_allclose(to_np(r["conf"]), ref["conf"][:Tm], rtol=2e-6)
+        e = rel_err(to_np(r["y"]), ref["y"][:Tm])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_DRAFT
+        if D2 is not None:      # the general format holding z = 8 computes the same sums
+            r2 = D2.draft(x[:Tm].cuda())
+            torch.cuda.synchronize()
+            assert torch.equal(r["ids"], r2["ids"])
+            assert rel_err(to_np(r2["y"]), to_np(r["y"])) <= 1e-5
+    del D, D2
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 def test_verify_layer(case):
     cfg = case.cfg
     for T in cfg.verify_tokens:

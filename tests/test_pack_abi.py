@@ -97,6 +97,38 @@ def test_int4_slice_layout_matches_the_header_formula():
             assert ent[i, 0] == bits(s["down"])[row, gi] and ent[i, 1] == bits(z["down"])[row, gi]
 
 
+def test_symmetric_scale_layout_matches_the_header_formula():
+    rng = np.random.default_rng(2)
+    H, I, g = 256, 96, 32
+    q = {n: torch.from_numpy(rng.integers(0, 16, shp).astype(np.uint8))
+         for n, shp in (("gate", (I, H)), ("up", (I, H)), ("down", (H, I)))}
+    s = {n: torch.from_numpy(rng.random((q[n].shape[0], q[n].shape[1] // g)).astype(np.float16)) for n in q}
+    qb, sb = pack.pack_int4_expert_symmetric(q, s)
+    z8 = {n: torch.full_like(s[n], 8.0) for n in s}
+    assert torch.equal(qb, pack.pack_int4_expert(q, s, z8)[0])       # the codes do not change
+    assert sb.numel() == 3 * H * I // g * 2
+    ent = sb.numpy().view("<u2")
+    G = H // g
+    bits = lambda t: t.numpy().view(np.uint16)
+    for row in range(I):
+        for gi in range(G):
+            d, r = (row % 32) // 16, row % 16
+            i = ((((row // 32) * (G // 2) + gi // 2) * 16 + r) * 2 + gi % 2) * 4 + d
+            assert ent[i] == bits(s["gate"])[row, gi] and ent[i + 2] == bits(s["up"])[row, gi]
+    base = (I // 32) * G * 64
+    for row in range(H):
+        for gi in range(I // g):
+            rt, d, r = row // 64, (row % 64) // 16, row % 16
+            i = base + (((gi * (H // 128) + rt // 2) * 16 + r) * 2 + rt % 2) * 4 + d
+            assert ent[i] == bits(s["down"])[row, gi]
+    d = B.LayerDesc(H, 4, 128, 2, 0, g, 1)
+    assert B.int4_expert_scale_bytes(d) == 3 * H * 128 // g * 2 == B.int4_expert_sz_bytes(d) // 2
+    # shapes the format cannot hold: an odd number of groups per row, or of 64-row tiles
+    assert B.int4_expert_scale_bytes(B.LayerDesc(384, 4, 128, 2, 0, 128, 1)) == 0
+    assert B.int4_expert_scale_bytes(B.LayerDesc(192, 4, 64, 2, 0, 32, 1)) == 0
+    assert B.int4_expert_sz_bytes(B.LayerDesc(192, 4, 64, 2, 0, 32, 1)) > 0
+
+
 def test_code_pairs_unpack_with_one_mask():
     # the property the kernel relies on: ((word >> 4j) & 0x000F000F) holds codes (2j, 2j+1)
     q = torch.zeros((64, 32), dtype=torch.uint8)

@@ -45,6 +45,23 @@ def test_rtn_quantiser_contract():
         assert torch.equal(q, q2) and torch.equal(s, s2) and torch.equal(z, z2)
 
 
+def test_symmetric_rtn_quantiser_contract():
+    rng = np.random.default_rng(1)
+    for g in (32, 128):
+        w = torch.from_numpy((0.02 * rng.standard_normal((16, 4 * g))).astype(np.float32)).to(torch.bfloat16)
+        w[0, :g] = 0
+        q, s, z = synth.quantize_rtn_int4_symmetric(w, g)
+        assert q.dtype == torch.uint8 and s.dtype == torch.float16 and z.dtype == torch.float16
+        assert bool((z == 8).all()) and int(q.max()) <= 15
+        assert float(s[0, 0]) == 1.0 and bool((q[0, :g] == 8).all())
+        deq = (q.double().reshape(16, 4, g) - 8.0) * s.double().unsqueeze(-1)
+        err = (deq.reshape(16, -1) - w.double()).abs().reshape(16, 4, g)
+        assert bool((err <= 0.5 * s.double().unsqueeze(-1) * 1.01).all())   # |w| <= 7 s up to fp16 rounding of s
+        # the largest magnitude of a live group lands on code 1 or 15 (-7 or +7)
+        top = (q.reshape(16, 4, g).to(torch.int32) - 8).abs().amax(-1)
+        assert bool((top[1:] == 7).all())
+
+
 def test_qwen3_tokens_repeat_about_30_percent_of_experts():
     cfg = synth.config_by_name("qwen3")
     wr = orc.bits(synth.make_router(cfg))
