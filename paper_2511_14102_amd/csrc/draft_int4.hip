@@ -130,20 +130,24 @@ struct FusedArgs {
 template <bool SYM> struct GroupParams;
 template <> struct GroupParams<false> {
     uint32_t w[4];
-    __device__ float scale(int d) const {
-        const uint32_t e = d == 0 ? w[0] : (d == 1 ? w[1] : (d == 2 ? w[2] : w[3]));
-        return (float)__builtin_bit_cast(_Float16, (uint16_t)(e & 0xffff));
+    // entry d; d may differ from lane to lane, so the choice is made with bit masks (a chain of
+    // conditional expressions on a lane-varying d was compiled into divergent branches)
+    __device__ uint32_t entry(int d) const {
+        const uint32_t m1 = 0u - (uint32_t)(d & 1), m2 = 0u - (uint32_t)((d >> 1) & 1);
+        const uint32_t lo = (w[1] & m1) | (w[0] & ~m1), hi = (w[3] & m1) | (w[2] & ~m1);
+        return (hi & m2) | (lo & ~m2);
     }
+    __device__ float scale(int d) const { return (float)__builtin_bit_cast(_Float16, (uint16_t)(entry(d) & 0xffff)); }
     __device__ float zero128(int d) const {                   // z + 128
-        const uint32_t e = d == 0 ? w[0] : (d == 1 ? w[1] : (d == 2 ? w[2] : w[3]));
-        return (float)__builtin_bit_cast(_Float16, (uint16_t)(e >> 16)) + 128.f;
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(entry(d) >> 16)) + 128.f;
     }
 };
 template <> struct GroupParams<true> {
     uint32_t w[2];
     __device__ float scale(int d) const {
-        const uint32_t e = (d >> 1) ? w[1] : w[0];
-        return (float)__builtin_bit_cast(_Float16, (uint16_t)((d & 1) ? e >> 16 : e & 0xffff));
+        const uint32_t m2 = 0u - (uint32_t)((d >> 1) & 1);
+        const uint32_t e = (w[1] & m2) | (w[0] & ~m2);
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(e >> (16 * (d & 1))));
     }
     __device__ float zero128(int) const { return 136.f; }
 };
@@ -360,6 +364,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             seen += pc;
         }
     }
+    expert = __builtin_amdgcn_readfirstlane(expert);   // the same in every lane; tell the compiler
     if (tid == 0) s_cnt = 0;
     if (tid < MT) s_hsum[tid] = 0.f;
     __syncthreads();
@@ -378,7 +383,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         if (lane == 0) s_cnt = cnt < MT ? cnt : MT;
     }
     __syncthreads();
-    const int cnt = s_cnt;
+    const int cnt = __builtin_amdgcn_readfirstlane(s_cnt);
 
     if (expert >= 0 && cnt > 0) {
         const int U = H / 32;
@@ -387,9 +392,12 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         const char *qb = a.q + (size_t)expert * a.stride_q;
         const char *szb = a.sz + (size_t)expert * a.stride_sz;
         // codes: [gate|up tiles (slice, ku)] then [down tiles (slice, rt)], 64 lanes x 16 B each
-        const u32x4 *qgu = reinterpret_cast<const u32x4 *>(qb) + (size_t)slice * U * 64 + lane;
-        const u32x4 *qd = reinterpret_cast<const u32x4 *>(qb) + (size_t)nslice * U * 64 +
-                          (size_t)slice * (H / 64) * 64 + lane;
+        // A tile's address is a wave-uniform base (scalar arithmetic) plus the lane's 16 bytes.
+        const int gu0 = slice * U, dn0 = nslice * U + slice * (H / 64);          // first tile of each part
+        const uint32_t lane_off = (uint32_t)lane * 16u;
+        auto tile_ptr = [&](int tile) {
+            return reinterpret_cast<const u32x4 *>(qb + (size_t)tile * 1024 + lane_off);
+        };
         // scale/zero: 16 B = the 4 row blocks' (s, z) of lane row r; [gate|up (slice, group)] then
         // [down (group of I, rt)]
         // (symmetric format: 16 B = the 4 row blocks' s of row r for two groups / two row tiles)
@@ -429,9 +437,9 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         auto stream_ptr = [&](int p) -> const u32x4 * {            // p: position in the stream
             const int ku = u0 + p;
             const int rt = r0 + (p - ntp);
-            const u32x4 *gp = qgu + (size_t)(ku < u1 ? ku : u1 - 1) * 64;
-            const u32x4 *dp = qd + (size_t)(rt < r1 ? rt : rt_last) * 64;
-            return p < ntp ? gp : dp;
+            const int gt = gu0 + (ku < u1 ? ku : u1 - 1);
+            const int dt = dn0 + (rt < r1 ? rt : rt_last);
+            return tile_ptr(p < ntp ? gt : dt);
         };
         // Scale/zero entries are fetched 4 kEpl groups (or row tiles) per load: lane group c
         // takes the 16 bytes of row r of load unit first / kEpl + 4 pk + c, and a lane picks the
@@ -475,7 +483,10 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG, pk));
         draw_ticket();
         u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (nt > 0 ? u0 : 0) * 32);
-        for (int base = 0; base < ntp; base += kGuWin) {
+        // one window of the gate/up part; kGuard: some of its tiles may lie past the wave's run (the
+        // padding of the last window) and are skipped.  Full windows carry no per-tile tests.
+        auto gu_window = [&](int base, auto guarded) {
+            constexpr bool kGuard = decltype(guarded)::value;
             u32x4 gsz_next[kSzPacks];                             // the next window's groups
 #pragma unroll
             for (int pk = 0; pk < kSzPacks; ++pk)
@@ -485,7 +496,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 const int pz = base + i, ku = u0 + pz;
                 const u32x4 qv = win[i];
                 win[i] = __builtin_nontemporal_load(stream_ptr(pz + kGuWin));
-                if (ku < u1) {
+                if (!kGuard || ku < u1) {
                     const u32x4 xn = *reinterpret_cast<const u32x4 *>(xrow + (ku + 1 < u1 ? ku + 1 : ku) * 32);
                     acc[0] = mfma(xa, unpack8(qv.x, uk), acc[0]);
                     acc[1] = mfma(xa, unpack8(qv.y, uk), acc[1]);
@@ -510,6 +521,11 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
 #pragma unroll
             for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = gsz_next[pk];
+        };
+        {
+            int base = 0;
+            for (; base + kGuWin <= nt; base += kGuWin) gu_window(base, std::false_type{});
+            if (base < ntp) gu_window(base, std::true_type{});
         }
         // the window now holds this wave's first kGuWin down tiles; their scales follow
         constexpr int kDPacks = (kGuWin + kPerPack - 1) / kPerPack;
@@ -518,9 +534,26 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             const int last = rt_last / kEpl;
             return szd + (size_t)(rt < last ? rt : last) * 16;
         };
+        // With one or two tokens a lane's D registers hold ONE row block of every down tile (its
+        // lane group's, see below), so it needs one entry per tile and loads that itself: no lane
+        // permutes and no selection among the four entries.
+        constexpr bool kOwnEntry = MT <= 2;
+        using entry_t = typename std::conditional<SYM, uint16_t, uint32_t>::type;
+        const entry_t *dent = reinterpret_cast<const entry_t *>(szb) + (size_t)nslice * G * 64 +
+                              (size_t)((slice * 32) / g) * nrt * 64 + (SYM ? r * 8 : r * 4) + c;
+        auto dent_load = [&](int rt) -> uint32_t {
+            const int t = rt < r1 ? rt : rt_last;
+            return (uint32_t)__builtin_nontemporal_load(dent + (SYM ? (t >> 1) * 128 + (t & 1) * 4 : t * 64));
+        };
         u32x4 dsz[kDPacks];
+        uint32_t dpe[kGuWin] = {};
+        if constexpr (kOwnEntry) {
 #pragma unroll
-        for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = __builtin_nontemporal_load(dsz_ptr(r0, pk));
+            for (int i = 0; i < kGuWin; ++i) dpe[i] = dent_load(r0 + i);
+        } else {
+#pragma unroll
+            for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = __builtin_nontemporal_load(dsz_ptr(r0, pk));
+        }
         if (c < NC) {
 #pragma unroll
             for (int d = 0; d < 4; ++d)
@@ -592,7 +625,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         auto down_pass = [&](int j0, auto reload) {
             constexpr bool kReload = decltype(reload)::value;
             u32x4 dsz_next[kDPacks];
-            if (kReload) {
+            if (kReload && !kOwnEntry) {
 #pragma unroll
                 for (int pk = 0; pk < kDPacks; ++pk)
                     dsz_next[pk] = __builtin_nontemporal_load(dsz_ptr(r0 + j0 + kGuWin, pk));
@@ -601,12 +634,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             for (int i = 0; i < kGuWin; ++i) {
                 const int rt = r0 + j0 + i;
                 const u32x4 qv = win[i];
+                const uint32_t ev = dpe[i];
                 if (kReload) {
                     const int rtn = rt + kGuWin;
-                    win[i] = __builtin_nontemporal_load(qd + (size_t)(rtn < r1 ? rtn : rt_last) * 64);
+                    win[i] = __builtin_nontemporal_load(tile_ptr(dn0 + (rtn < r1 ? rtn : rt_last)));
+                    if constexpr (kOwnEntry) dpe[i] = dent_load(rtn);
                 }
                 if (rt < r1) {
-                    const GroupParams<SYM> gp = pick(dsz, i);
+                    GroupParams<SYM> gp;
+                    if constexpr (!kOwnEntry) gp = pick(dsz, i);
                     const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
 #pragma unroll
                     for (int q = 0; q < 4 / kBpa; ++q) {
@@ -614,7 +650,14 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
                         for (int bl = 0; bl < kBpa; ++bl) o = mfma(hab[bl], unpack8(qw[q * kBpa + bl], uk), o);
                         const int d = q * kBpa + my_bl;          // this lane's row block of the tile
-                        const float sc = gp.scale(d), zp = gp.zero128(d);
+                        float sc, zp;
+                        if constexpr (kOwnEntry) {
+                            sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(ev & 0xffff));
+                            zp = SYM ? 136.f : (float)__builtin_bit_cast(_Float16, (uint16_t)(ev >> 16)) + 128.f;
+                        } else {
+                            sc = gp.scale(d);
+                            zp = gp.zero128(d);
+                        }
 #pragma unroll
                         for (int j = 0; j < ND; ++j) {
                             if (live[j]) {
@@ -626,7 +669,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     }
                 }
             }
-            if (kReload) {
+            if (kReload && !kOwnEntry) {
 #pragma unroll
                 for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = dsz_next[pk];
             }
