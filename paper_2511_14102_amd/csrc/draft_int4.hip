@@ -476,11 +476,36 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
             for (int i = 0; i < NI; ++i) tot[d][i] = 0.f;
         }
+        // With ONE token all 16 A rows hold that token, so every lane group ends up with the same
+        // sums.  Lane group c then finishes row block c only: it loads that block's entry itself
+        // (no lane permutes), picks accumulator c and applies scale and zero to one value instead
+        // of four.
+        constexpr bool kOwnGu = MT == 1;
+        using gentry_t = typename std::conditional<SYM, uint16_t, uint32_t>::type;
+        const gentry_t *gent_base = reinterpret_cast<const gentry_t *>(szb) + (size_t)slice * G * 64 +
+                                    (SYM ? r * 8 : r * 4) + c;
+        auto gent_load = [&](int gi) -> uint32_t {
+            const int t = gi < g_last ? gi : g_last;
+            return (uint32_t)__builtin_nontemporal_load(gent_base + (SYM ? (t >> 1) * 128 + (t & 1) * 4 : t * 64));
+        };
+        const uint32_t cm1 = 0u - (uint32_t)(c & 1), cm2 = 0u - (uint32_t)(c >> 1);
+        auto of_my_block = [&](float v0, float v1, float v2, float v3) {   // v_c, chosen with bit masks
+            const uint32_t lo = (__float_as_uint(v1) & cm1) | (__float_as_uint(v0) & ~cm1);
+            const uint32_t hi = (__float_as_uint(v3) & cm1) | (__float_as_uint(v2) & ~cm1);
+            return __uint_as_float((hi & cm2) | (lo & ~cm2));
+        };
+        float tot1 = 0.f;
         u32x4 win[kGuWin], gsz[kSzPacks];
+        uint32_t gent[kSzWin] = {};
 #pragma unroll
         for (int i = 0; i < kGuWin; ++i) win[i] = __builtin_nontemporal_load(stream_ptr(i));
+        if constexpr (kOwnGu) {
 #pragma unroll
-        for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG, pk));
+            for (int j = 0; j < kSzWin; ++j) gent[j] = gent_load(u0 / UPG + j);
+        } else {
+#pragma unroll
+            for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG, pk));
+        }
         draw_ticket();
         u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (nt > 0 ? u0 : 0) * 32);
         // one window of the gate/up part; kGuard: some of its tiles may lie past the wave's run (the
@@ -488,9 +513,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         auto gu_window = [&](int base, auto guarded) {
             constexpr bool kGuard = decltype(guarded)::value;
             u32x4 gsz_next[kSzPacks];                             // the next window's groups
+            uint32_t gent_next[kSzWin];
+            if constexpr (kOwnGu) {
 #pragma unroll
-            for (int pk = 0; pk < kSzPacks; ++pk)
-                gsz_next[pk] = __builtin_nontemporal_load(gsz_ptr((u0 + base) / UPG + kSzWin, pk));
+                for (int j = 0; j < kSzWin; ++j) gent_next[j] = gent_load((u0 + base) / UPG + kSzWin + j);
+            } else {
+#pragma unroll
+                for (int pk = 0; pk < kSzPacks; ++pk)
+                    gsz_next[pk] = __builtin_nontemporal_load(gsz_ptr((u0 + base) / UPG + kSzWin, pk));
+            }
 #pragma unroll
             for (int i = 0; i < kGuWin; ++i) {
                 const int pz = base + i, ku = u0 + pz;
@@ -505,22 +536,36 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                     xa = xn;
                     if (i % UPG == UPG - 1) {                 // end of a group: scale / zero / offset
                         const int gi = ku / UPG;
-                        const GroupParams<SYM> gp = pick(gsz, i / UPG);
                         float xs[NI];
 #pragma unroll
                         for (int j = 0; j < NI; ++j) xs[j] = s_xsum[tok[j] * G + gi];
+                        if constexpr (kOwnGu) {
+                            const uint32_t ev = gent[i / UPG];
+                            const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(ev & 0xffff));
+                            const float zp = SYM ? 136.f : (float)__builtin_bit_cast(_Float16, (uint16_t)(ev >> 16)) + 128.f;
+                            tot1 += sc * (of_my_block(acc[0][0], acc[1][0], acc[2][0], acc[3][0]) - zp * xs[0]);
 #pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            const float sc = gp.scale(d), zp = gp.zero128(d);
+                            for (int d = 0; d < 4; ++d) acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                        } else {
+                            const GroupParams<SYM> gp = pick(gsz, i / UPG);
 #pragma unroll
-                            for (int j = 0; j < NI; ++j) tot[d][j] += sc * (acc[d][j] - zp * xs[j]);
-                            acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                            for (int d = 0; d < 4; ++d) {
+                                const float sc = gp.scale(d), zp = gp.zero128(d);
+#pragma unroll
+                                for (int j = 0; j < NI; ++j) tot[d][j] += sc * (acc[d][j] - zp * xs[j]);
+                                acc[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                            }
                         }
                     }
                 }
             }
+            if constexpr (kOwnGu) {
 #pragma unroll
-            for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = gsz_next[pk];
+                for (int j = 0; j < kSzWin; ++j) gent[j] = gent_next[j];
+            } else {
+#pragma unroll
+                for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = gsz_next[pk];
+            }
         };
         {
             int base = 0;
@@ -554,7 +599,9 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
             for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = __builtin_nontemporal_load(dsz_ptr(r0, pk));
         }
-        if (c < NC) {
+        if constexpr (kOwnGu) {
+            s_red[wave][c][0][r] = tot1;
+        } else if (c < NC) {
 #pragma unroll
             for (int d = 0; d < 4; ++d)
 #pragma unroll
