@@ -279,6 +279,68 @@ def resident_leg(args, cfg, ctx, dev):
 
 
 # ------------------------------------------------------------------------------------------------
+def prefill_leg(args, cfg, ctx, dev):
+    """--prefill T: the draft layer over T tokens in one call (moe_draft_prefill_int4), rotating over
+    distinct layers.  A side measurement, not the headline metric: a step is one call."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2511_14102_amd.harness import DeviceLayer
+
+    T = args.prefill
+    n_layers = args.layers or 4
+    sym = args.int4 == "symmetric"
+    L0 = synth.make_layer(cfg, 0, quant_device=dev, symmetric=sym)
+    layers = []
+    for li in range(n_layers):
+        L = L0 if li == 0 else synth.make_layer(cfg, li, device=dev, symmetric=sym)
+        layers.append(DeviceLayer(ctx, cfg, L, max_tokens=8, verify=False, symmetric=sym))
+    x = synth.make_tokens(cfg, T, kind="iid").to(dev)
+    H, k = cfg.hidden, cfg.top_k
+    y = torch.empty((T, H), dtype=torch.float32, device=dev)
+    ids = torch.empty((T, k), dtype=torch.int32, device=dev)
+    conf = torch.empty((T, k), dtype=torch.float32, device=dev)
+    for i in range(args.warmup):
+        layers[i % n_layers].prefill(x, y=y, ids=ids, conf=conf)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        layers[(args.warmup + i) % n_layers].prefill(x, y=y, ids=ids, conf=conf)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    ctx.profile_enable(True)
+    for i in range(min(args.steps, 8)):
+        layers[i % n_layers].prefill(x, y=y, ids=ids, conf=conf)
+    torch.cuda.synchronize()
+    kern = read_profile(ctx)
+    ctx.profile_enable(False)
+    cnt = np.bincount(ids.cpu().numpy().reshape(-1), minlength=cfg.n_experts)
+    items = int(np.sum((cnt + 7) // 8))
+    P = 3 * H * cfg.inter
+    expert_bytes = P // 2 + (P // cfg.group_size) * (2 if sym else 4)
+    us = kern["draft_fused_kernel"]["us_avg"]
+    out = {"metric": "draft prefill tokens/s per MoE layer, 1 GPU", "value": round(T / (ms * 1e-3), 1), "unit": "tokens/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "dtype": "int4 (fp32 accumulate)", "data": "synthetic",
+           "config": {"workload": "%s-shaped MoE layer, one moe_draft_prefill_int4 call over %d tokens, %d distinct layers"
+                                  % (cfg.name, T, n_layers)},
+           "us_per_token": round(ms * 1e3 / T, 3),
+           "work_items": items, "distinct_experts": int((cnt > 0).sum()),
+           "kernel_us": {n: round(v["us_avg"], 2) for n, v in kern.items()},
+           "weights_streamed": {"bytes_per_call": items * expert_bytes, "GBs": round(items * expert_bytes / us / 1e3, 1),
+                                "note": "every expert's weights are read once per 8 of its assignments"},
+           "roofline": {"kernel": "draft_fused_kernel (prerouted)", "bound": "hbm",
+                        "achieved": round(int((cnt > 0).sum()) * expert_bytes / us / 1e3, 1), "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": round(int((cnt > 0).sum()) * expert_bytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                        "traffic": None,
+                        "note": "algorithmic bytes = each distinct expert once; the kernel re-reads an expert per "
+                                "item and is limited by the fp32 atomics into y (T k H I / 32 of them)"}}
+    print(json.dumps(out), flush=True)
+
+
+# ------------------------------------------------------------------------------------------------
 def offload_leg(args, cfg, ctx, dev):
     """n_resident of the E experts of every layer start in the expert cache; all experts also sit in
     pinned host memory.  The Expert Scheduler (moe_elb_*, moe_cache_*, moe_sched_*) decides what
@@ -553,6 +615,8 @@ def main():
                     help="how the timed steps are launched (per-kernel timing always runs eagerly)")
     ap.add_argument("--int4", default="asymmetric", choices=["asymmetric", "symmetric"],
                     help="draft weight format: scale + zero per group (default) or scales only with z = 8")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="side measurement: one moe_draft_prefill_int4 call over this many tokens per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--slots", type=int, default=0,
@@ -573,7 +637,9 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.config_by_name(args.config)
     ctx = B.Context(0)
-    if cfg.n_resident and cfg.n_resident < cfg.n_experts:
+    if args.prefill:
+        prefill_leg(args, cfg, ctx, "cuda:0")
+    elif cfg.n_resident and cfg.n_resident < cfg.n_experts:
         offload_leg(args, cfg, ctx, "cuda:0")
     else:
         resident_leg(args, cfg, ctx, "cuda:0")

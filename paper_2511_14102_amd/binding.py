@@ -19,7 +19,8 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_MISSING_EXP
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_status_string", "moe_last_hip_error", "moe_validate_desc",
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
-    "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk", "moe_draft_layer_int4", "moe_expert_union",
+    "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
+    "moe_draft_layer_int4", "moe_prefill_workspace_bytes", "moe_draft_prefill_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
     "moe_profile_enable", "moe_profile_read", "moe_kernel_name", "moe_stream_read_probe",
 ]
@@ -84,6 +85,9 @@ def load_library():
         L.moe_route_topk.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_draft_layer_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                            vp, vp, vp, vp, sz, vp]
+        L.moe_prefill_workspace_bytes.argtypes = [dp, i32, ctypes.POINTER(sz)]
+        L.moe_draft_prefill_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), i32,
+                                             vp, vp, vp, vp, sz, vp]
         L.moe_expert_union.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_verify_layer_bf16.argtypes = [vp, dp, vp, vp, vp, vp, sz, vp, vp, i32, i32,
                                             vp, vp, vp, vp, vp, sz, vp]
@@ -131,6 +135,14 @@ def workspace_bytes(desc: LayerDesc, max_tokens: int) -> int:
     rc = load_library().moe_workspace_bytes(ctypes.byref(desc), max_tokens, ctypes.byref(out))
     if rc != MOE_OK:
         raise MoeError(rc, "moe_workspace_bytes")
+    return out.value
+
+
+def prefill_workspace_bytes(desc: LayerDesc, T: int) -> int:
+    out = ctypes.c_size_t(0)
+    rc = load_library().moe_prefill_workspace_bytes(ctypes.byref(desc), T, ctypes.byref(out))
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_prefill_workspace_bytes")
     return out.value
 
 
@@ -194,6 +206,14 @@ class Context:
             self._h, ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), ctypes.byref(ex),
             _ptr(shared_bf16), T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)), "moe_draft_layer_int4")
+
+    def draft_prefill_int4(self, desc, x, w_router, router_bias, q_blob, sz_blob, stride_q, stride_sz,
+                           T, y_f32, ids_out, conf_out, workspace, stream=None, symmetric=False):
+        ex = Int4Experts(q_blob.data_ptr(), sz_blob.data_ptr(), stride_q, stride_sz, int(bool(symmetric)))
+        self._check(self._lib.moe_draft_prefill_int4(
+            self._h, ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), ctypes.byref(ex),
+            T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream(stream)), "moe_draft_prefill_int4")
 
     def expert_union(self, ids, n_ids, n_experts, slot_of_expert, mask, lst, n_list, missing,
                      n_missing, stream=None):

@@ -295,6 +295,7 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
     DraftFusedArgs a;
+    memset(&a, 0, sizeof a);
     a.x = x; a.wr = wr; a.bias = bias;
     a.q = routed->q; a.sz = routed->sz;
     a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
@@ -313,6 +314,80 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
           launch_combine(s, plan, nullptr, 0, (const float *)(ws + L.obuf), 1, 0, y, st); }
     }
+    return hip_status(ctx, hipGetLastError());
+}
+
+// workspace of a prefill call: routing weights and sorted assignment indices [T k], the item
+// count (one 256-byte line) and the items
+struct PrefillLayout { size_t w_all, sorted, n_items, items, total; int max_items; };
+static PrefillLayout prefill_layout(const moe_layer_desc &d, int T)
+{
+    PrefillLayout L;
+    const size_t n = (size_t)T * d.top_k;
+    // sum over experts of ceil(count / chunk) <= n / chunk + number of experts that occur
+    L.max_items = (int)(n / kPrefillChunk + ((size_t)d.n_experts < n ? (size_t)d.n_experts : n));
+    size_t o = 0;
+    L.w_all = o;   o += align256(n * 4);
+    L.sorted = o;  o += align256(n * 4);
+    L.n_items = o; o += 256;
+    L.items = o;   o += align256((size_t)L.max_items * sizeof(PrefillItem));
+    L.total = o;
+    return L;
+}
+
+static int check_prefill(const moe_layer_desc *d, int T)
+{
+    if (check_desc(d) != MOE_OK || d->n_shared != 0) return MOE_ERR_INVALID_ARG;
+    if (T < 1 || T > MOE_MAX_PREFILL_TOKENS) return MOE_ERR_INVALID_ARG;
+    return MOE_OK;
+}
+
+int moe_prefill_workspace_bytes(const moe_layer_desc *desc, int T, size_t *bytes)
+{
+    if (!bytes || check_prefill(desc, T) != MOE_OK) return MOE_ERR_INVALID_ARG;
+    *bytes = prefill_layout(*desc, T).total;
+    return MOE_OK;
+}
+
+int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
+                           const void *x, const void *wr, const float *bias,
+                           const moe_int4_experts *routed, int T,
+                           float *y, int32_t *ids_out, float *conf_out,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || check_prefill(desc, T) != MOE_OK) return MOE_ERR_INVALID_ARG;
+    if (!x || !wr || !routed || !routed->q || !routed->sz || !y || !ids_out)
+        return MOE_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(wr, 16) || !aligned(bias, 4) || !aligned(routed->q, 16) ||
+        !aligned(routed->sz, 16) || routed->expert_stride_q % 16 || routed->expert_stride_sz % 16 ||
+        !aligned(y, 16) || !aligned(ids_out, 4) || !aligned(conf_out, 4))
+        return MOE_ERR_INVALID_ARG;
+    const size_t sz_bytes = routed->symmetric ? moe_int4_expert_scale_bytes(desc) : moe_int4_expert_sz_bytes(desc);
+    if (sz_bytes == 0 || routed->expert_stride_q < moe_int4_expert_q_bytes(desc) ||
+        routed->expert_stride_sz < sz_bytes)
+        return MOE_ERR_INVALID_ARG;
+    const PrefillLayout L = prefill_layout(*desc, T);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+
+    const Shape s = make_shape(desc, T);
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    float *w_all = (float *)(ws + L.w_all);
+    int32_t *sorted = (int32_t *)(ws + L.sorted);
+    int32_t *n_items = (int32_t *)(ws + L.n_items);
+    PrefillItem *items = (PrefillItem *)(ws + L.items);
+    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st); launch_route(s, x, wr, bias, ids_out, w_all, conf_out, st); }
+    launch_zero(y, (size_t)T * s.H * 4, st);
+    { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_prefill_plan(ids_out, T * s.k, s.E, sorted, items, n_items, st); }
+    DraftFusedArgs a;
+    memset(&a, 0, sizeof a);
+    a.x = x; a.wr = wr; a.bias = bias;
+    a.q = routed->q; a.sz = routed->sz;
+    a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
+    a.symmetric = routed->symmetric ? 1 : 0;
+    a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
+    a.items = items; a.n_items = n_items; a.sorted = sorted; a.w_all = w_all;
+    { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_prerouted(s, a, L.max_items, st); }
     return hip_status(ctx, hipGetLastError());
 }
 

@@ -122,6 +122,12 @@ struct FusedArgs {
     Plan *plan;                 // filled for the shared-expert kernels when S > 0
     const char *shared;         // bf16 shared expert blobs
     size_t shared_stride;
+    // already routed call (a long run of tokens): work items, their number, the assignment indices
+    // sorted by expert, and the routing weight of every assignment
+    const PrefillItem *items;
+    const int32_t *n_items;
+    const int32_t *sorted;
+    const float *w_all;
     int T, H, E, I, k, g, S, renorm;
 };
 
@@ -153,8 +159,12 @@ template <> struct GroupParams<true> {
 };
 
 // MT: token capacity of the launch (1, 2, 4 or 8); UPG: 32-code units per group (g / 32); SYM:
-// symmetric format (scale blobs, z = 8).
-template <int MT, int UPG, bool SYM>
+// symmetric format (scale blobs, z = 8).  PRE: the tokens are already routed and sorted by expert
+// (a prompt, or any run of more than MOE_MAX_DRAFT_TOKENS tokens): workgroup b takes slice
+// b % (I / 32) of work item b / (I / 32) from a list, an item being up to MT assignments of one
+// expert; its rows are gathered from x, y has been cleared by the caller, and the router
+// exchange (phases 1, 2, 4, 5) does not take place.
+template <int MT, int UPG, bool SYM, bool PRE>
 __global__ __launch_bounds__(kThreads, MT <= 2 ? 4 : 2)   // MT <= 2: 4 waves per SIMD, two workgroups per CU
 void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 {
@@ -186,13 +196,22 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     const int xstride = H + 8;                   // bf16 elements per token in LDS (+16 B against bank conflicts)
     uint16_t *s_x = reinterpret_cast<uint16_t *>(s_dyn);
     float *s_xsum = reinterpret_cast<float *>(s_dyn + (size_t)MT * xstride * 2);   // [MT][G]
+    int pre_expert = -1, pre_cnt = 0;
+    if constexpr (PRE) {
+        const int item = blockIdx.x / (I / 32);
+        if (item >= *a.n_items) return;                   // the grid is sized for the largest possible list
+        const PrefillItem it = a.items[item];
+        pre_expert = it.expert;
+        pre_cnt = it.cnt < MT ? it.cnt : MT;
+        if (tid < MT) s_row_a[tid] = a.sorted[it.first + (tid < pre_cnt ? tid : 0)];
+    }
     // ---- 1. router rows owned by this workgroup (fp64 accumulation of exact fp32 products)
-    if ((int)blockIdx.x < E) {
+    if (!PRE && (int)blockIdx.x < E) {
         const int nprod = E < (int)gridDim.x ? E : (int)gridDim.x;
         for (int i = blockIdx.x * kThreads + tid; i < T * H; i += nprod * kThreads)
             __hip_atomic_store(&a.y[i], 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    for (int e = blockIdx.x; e < E; e += gridDim.x) {
+    for (int e = blockIdx.x; !PRE && e < E; e += gridDim.x) {
         const uint16_t *row = a.wr + (size_t)e * H;
         for (int t = 0; t < T; ++t) {
             const uint16_t *xt = xin + (size_t)t * H;
@@ -232,12 +251,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     __syncthreads();
 
     // ---- 1b. (while the router result travels) stage x in LDS and sum it per group
-    for (int i = tid; i < T * (H / 8); i += kThreads) {
+    // (PRE: LDS row j is the token of the item's j-th assignment)
+    const int Ts = PRE ? pre_cnt : T;
+    for (int i = tid; i < Ts * (H / 8); i += kThreads) {
         const int t = i / (H / 8), c8 = i % (H / 8);
-        *reinterpret_cast<u32x4 *>(s_x + t * xstride + c8 * 8) = *reinterpret_cast<const u32x4 *>(xin + (size_t)t * H + c8 * 8);
+        const int src = PRE ? s_row_a[t] / k : t;
+        *reinterpret_cast<u32x4 *>(s_x + t * xstride + c8 * 8) = *reinterpret_cast<const u32x4 *>(xin + (size_t)src * H + c8 * 8);
     }
     __syncthreads();
-    for (int i = tid; i < T * G * 16; i += kThreads) {       // 16 threads per (token, group)
+    for (int i = tid; i < Ts * G * 16; i += kThreads) {       // 16 threads per (token, group)
         const int part = i & 15, tg_ = i >> 4;
         const int t = tg_ / G, gi = tg_ % G;
         const int per = g / 16;                               // 2, 4 or 8 values each
@@ -249,7 +271,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     }
 
     // ---- 2. wave t polls the slots of token t (bounded), then selects its top-k
-    for (int t = wave; t < T; t += kWaves) {
+    for (int t = wave; !PRE && t < T; t += kWaves) {
         double l[4];
         {
             uint32_t spins = 0;
@@ -336,7 +358,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
     __syncthreads();
-    const bool ok = s_flag != 0;
+    const bool ok = PRE || s_flag != 0;
     // This workgroup will not look at the slots again: it draws a ticket.  The tickets are
     // two-level (kTicketGroups first-level counters, then one) so that the returning atomics do
     // not queue up on one address, and the atomic is issued by the last wave only after its
@@ -344,15 +366,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     // otherwise hold back that wave's weight loads (measured: up to 5 us with one counter).
     uint32_t ticket = 0xffffffffu;
     auto draw_ticket = [&]() {
-        if (tid == kThreads - 64)
+        if (!PRE && tid == kThreads - 64)
             ticket = __hip_atomic_fetch_add(a.tickets + blockIdx.x % kTicketGroups, 1u, __ATOMIC_RELAXED,
                                             __HIP_MEMORY_SCOPE_AGENT);
     };
     // ---- 3. this workgroup's item: the u-th distinct expert (ascending id), slice s
     const int nslice = I / 32;
     const int u = blockIdx.x / nslice, slice = blockIdx.x % nslice;
-    int expert = -1;
-    if (ok) {
+    int expert = pre_expert;
+    if (!PRE && ok) {
         int seen = 0;
         for (int wd = 0; wd < MOE_MAX_EXPERTS / 64 && expert < 0; ++wd) {
             unsigned long long mk = s_mask[wd];
@@ -365,10 +387,10 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
     expert = __builtin_amdgcn_readfirstlane(expert);   // the same in every lane; tell the compiler
-    if (tid == 0) s_cnt = 0;
+    if (tid == 0) s_cnt = pre_cnt;
     if (tid < MT) s_hsum[tid] = 0.f;
     __syncthreads();
-    if (expert >= 0 && wave == 0) {             // rows of the item: assignments with this expert, ascending
+    if (!PRE && expert >= 0 && wave == 0) {     // rows of the item: assignments with this expert, ascending
         int cnt = 0;
         for (int base = 0; base < n; base += 64) {
             const int aidx = base + lane;
@@ -407,17 +429,14 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                            (size_t)((slice * 32) / g) * (H / (64 * kEpl)) * 16 + r;
 
         // A-operand row of this lane: token slot r (slots >= cnt repeat slot 0; their D rows are ignored)
-        const int my_tok = s_row_a[r < cnt ? r : 0] / k;
-        const uint16_t *xrow = s_x + my_tok * xstride + c * 8;
+        auto lds_row = [&](int slot) { return PRE ? slot : s_row_a[slot] / k; };   // where the slot's x was staged
+        const uint16_t *xrow = s_x + lds_row(r < cnt ? r : 0) * xstride + c * 8;
         // tokens whose results this lane holds in its D registers: slot 4c + i
         int tok[NI];
-        float rw[NI];
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int slot = 4 * c + i;
-            const int arow = s_row_a[slot < cnt ? slot : 0];
-            tok[i] = arow / k;
-            rw[i] = s_w[arow];
+            tok[i] = lds_row(slot < cnt ? slot : 0);
         }
 
         // ---- this wave's tile stream: its gate/up tiles u0 .. u1 (K = H split over the waves by
@@ -665,7 +684,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             live[i] = t < cnt;
             hsum[i] = s_hsum[slot];
             tokd[i] = arow / k;
-            rwd[i] = s_w[arow];
+            rwd[i] = PRE ? a.w_all[arow] : s_w[arow];
         }
         // one pass over the window: kReload: the slot is refilled with the tile kGuWin further on
         // (clamped, unconditional); the last pass refills nothing
@@ -730,6 +749,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     else {
         draw_ticket();
     }
+    if constexpr (PRE) return;
     // ---- 4. last ticket: every workgroup has its logits, put the workspace back to idle
     if (tid == kThreads - 64) {
         const uint32_t grp = blockIdx.x % kTicketGroups;
@@ -828,16 +848,16 @@ void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st
     launch(kernel, grid, block, lds, st, x, a);
 }
 
-template <int MT, bool SYM>
-void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st)
+template <int MT, bool SYM, bool PRE = false>
+void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st, int max_items = 0)
 {
-    const int maxu = a.E < a.T * a.k ? a.E : a.T * a.k;
+    const int maxu = PRE ? max_items : (a.E < a.T * a.k ? a.E : a.T * a.k);
     const dim3 grid(maxu * (a.I / 32)), block(kThreads);
     // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums
     const size_t lds = (size_t)MT * (a.H + 8) * 2 + (size_t)MT * (a.H / a.g) * 4;
-    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM>, grid, block, lds, st, x, a);
-    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM>, grid, block, lds, st, x, a);
-    else launch_with_lds(draft_fused_kernel<MT, 4, SYM>, grid, block, lds, st, x, a);
+    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM, PRE>, grid, block, lds, st, x, a);
+    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM, PRE>, grid, block, lds, st, x, a);
+    else launch_with_lds(draft_fused_kernel<MT, 4, SYM, PRE>, grid, block, lds, st, x, a);
 }
 
 template <bool SYM>
@@ -851,18 +871,33 @@ void launch_fused(int T, const uint16_t *x, const FusedArgs &a, hipStream_t st)
 
 }  // namespace
 
-void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
+static FusedArgs fused_args(const Shape &s, const DraftFusedArgs &d)
 {
     FusedArgs a;
-    const uint16_t *x = (const uint16_t *)d.x;
     a.wr = (const uint16_t *)d.wr; a.bias = d.bias;
     a.q = (const char *)d.q; a.sz = (const char *)d.sz; a.stride_q = d.stride_q; a.stride_sz = d.stride_sz;
     a.slots = d.slots; a.replica_stride = d.replica_stride; a.tickets = d.tickets; a.y = d.y;
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
+    a.items = d.items; a.n_items = d.n_items; a.sorted = d.sorted; a.w_all = d.w_all;
     a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;
+    return a;
+}
+
+void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
+{
+    const FusedArgs a = fused_args(s, d);
+    const uint16_t *x = (const uint16_t *)d.x;
     if (d.symmetric) launch_fused<true>(s.T, x, a, st);
     else launch_fused<false>(s.T, x, a, st);
+}
+
+void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &d, int max_items, hipStream_t st)
+{
+    const FusedArgs a = fused_args(s, d);
+    const uint16_t *x = (const uint16_t *)d.x;
+    if (d.symmetric) launch_fused_t<kPrefillChunk, true, true>(x, a, st, max_items);
+    else launch_fused_t<kPrefillChunk, false, true>(x, a, st, max_items);
 }
 
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st)

@@ -91,9 +91,17 @@ void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st);
 // router + plan in one launch; arrivals: 4-byte counter in the workspace, zero between launches
 void launch_route_plan(const Shape &s, const void *x, const void *wr, const float *bias, const PlanArgs &a,
                        uint32_t *arrivals, hipStream_t st);
+struct PrefillItem;
+void launch_prefill_plan(const int32_t *ids, int n, int E, int32_t *sorted, PrefillItem *items,
+                         int32_t *n_items, hipStream_t st);
 void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
                   uint64_t *mask, int32_t *list, int32_t *n_list,
                   int32_t *missing, int32_t *n_missing, hipStream_t st);
+
+// Work item of an already routed draft call: up to kPrefillChunk assignments of one expert,
+// sorted[first .. first + cnt).
+constexpr int kPrefillChunk = 8;
+struct PrefillItem { int32_t expert, first, cnt, pad; };
 
 // draft_int4.hip
 struct DraftFusedArgs {
@@ -103,8 +111,11 @@ struct DraftFusedArgs {
     unsigned long long *slots; size_t replica_stride; uint32_t *tickets;
     float *y; int32_t *ids_out; float *conf_out;
     Plan *plan; const void *shared; size_t shared_stride;
+    const PrefillItem *items; const int32_t *n_items; const int32_t *sorted; const float *w_all;   // prerouted only
 };
 void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
+// grid sized for max_items work items; y must have been cleared
+void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &a, int max_items, hipStream_t st);
 void launch_zero(void *p, size_t bytes, hipStream_t st);
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st);
 

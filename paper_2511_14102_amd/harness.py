@@ -111,6 +111,21 @@ class DeviceLayer:
                                   self.workspace, stream, symmetric=self.symmetric)
         return dict(y=y, ids=ids, conf=conf)
 
+    def prefill(self, x: torch.Tensor, y=None, ids=None, conf=None, stream=None):
+        """The draft layer over a long run of tokens (moe_draft_prefill_int4)."""
+        T, k = x.shape[0], self.cfg.top_k
+        dev = self.dev
+        y = torch.empty((T, self.cfg.hidden), dtype=torch.float32, device=dev) if y is None else y
+        ids = torch.empty((T, k), dtype=torch.int32, device=dev) if ids is None else ids
+        conf = torch.empty((T, k), dtype=torch.float32, device=dev) if conf is None else conf
+        need = B.prefill_workspace_bytes(self.desc, T)
+        if getattr(self, "_prefill_ws", None) is None or self._prefill_ws.numel() < need:
+            self._prefill_ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.ctx.draft_prefill_int4(self.desc, x, self.router, self.bias, self.q_blob, self.sz_blob,
+                                    self.q_bytes, self.sz_bytes, T, y, ids, conf, self._prefill_ws,
+                                    stream, symmetric=self.symmetric)
+        return dict(y=y, ids=ids, conf=conf)
+
     def verify(self, x: torch.Tensor, flags: int = 0, y=None, ids=None, stream=None):
         T, k = x.shape[0], self.cfg.top_k
         dev = self.dev

@@ -149,6 +149,44 @@ def test_draft_layer_symmetric_format(ctx, name):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name,tokens", [("tiny", (1, 9, 37, 200)), ("qwen3", (40,)), ("phi", (48,))])
+def test_draft_prefill(ctx, name, tokens):
+    # many tokens in one call: routed first, grouped by expert, 8 assignments of an expert per item
+    cfg = synth.config_by_name(name)
+    say("building", cfg.name, "for prefill")
+    L = build_layer(cfg)
+    A = oracle_arrays(L)
+    D = DeviceLayer(ctx, cfg, L, max_tokens=8, verify=False)
+    torch.cuda.synchronize()
+    for T in tokens:
+        x = tokens_with_clear_routing(cfg, A, T, step=30 + T, kind="iid")
+        ref = oracle_draft(A, x)
+        say("prefill", cfg.name, "T", T)
+        r = D.prefill(x.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"])
+        np.testing.assert_allclose(to_np(r["conf"]), ref["conf"], rtol=2e-6)
+        e = rel_err(to_np(r["y"]), ref["y"])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_DRAFT
+        if T <= 8:                       # the same tokens through the one-launch draft call
+            r1 = D.draft(x.cuda())
+            torch.cuda.synchronize()
+            assert torch.equal(r1["ids"], r["ids"])
+            assert rel_err(to_np(r1["y"]), to_np(r["y"])) <= 1e-5
+    # a second call reuses the workspace (nothing is carried over) and a draft call still works after it
+    r2 = D.prefill(x.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(r2["ids"], r["ids"]) and rel_err(to_np(r2["y"]), to_np(r["y"])) <= 1e-5
+    r3 = D.draft(x[:1].cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(r3["ids"]), ref["ids"][:1])
+    assert rel_err(to_np(r3["y"]), ref["y"][:1]) <= TOL_DRAFT
+    del D
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 def test_verify_layer(case):
     cfg = case.cfg
     for T in cfg.verify_tokens:
