@@ -216,10 +216,11 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
 /*
  * The draft model over a long run of tokens (the prompt; section 3.4.2-3.4.3 describe the same
  * int4 layer, section 3.1 the draft model that has to consume the prompt before it can
- * speculate).  Same mathematics and outputs as moe_draft_layer_int4 for 1 <= T <=
- * MOE_MAX_PREFILL_TOKENS tokens, desc->n_shared == 0 (else MOE_ERR_INVALID_ARG).  All tokens are
- * routed first, the assignments are grouped by expert, and every expert's weights are streamed
- * once per 8 of its assignments (a token-by-token loop streams them once per assignment).
+ * speculate).  Same mathematics, arguments and outputs as moe_draft_layer_int4 for 1 <= T <=
+ * MOE_MAX_PREFILL_TOKENS tokens.  All tokens are routed first, the assignments are grouped by
+ * expert, and every expert's weights are streamed once per 8 of its assignments (a
+ * token-by-token loop streams them once per assignment); shared experts run over chunks of up
+ * to 16 tokens.
  * ids_out [T,k] and conf_out [T,k] (or NULL) as in moe_draft_layer_int4; y_f32 [T,H] is
  * cleared and then summed with fp32 atomics.  workspace: moe_prefill_workspace_bytes(desc, T)
  * bytes, 256-byte aligned, no state is kept in it between calls.
@@ -228,7 +229,7 @@ int moe_prefill_workspace_bytes(const moe_layer_desc *desc, int T, size_t *bytes
 int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
                            const void *x_bf16, const void *w_router_bf16,
                            const float *router_bias,
-                           const moe_int4_experts *routed,
+                           const moe_int4_experts *routed, const void *shared_bf16,
                            int T,
                            float *y_f32, int32_t *ids_out, float *conf_out,
                            void *workspace, size_t workspace_bytes, void *stream);

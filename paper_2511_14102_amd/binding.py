@@ -86,7 +86,7 @@ def load_library():
         L.moe_draft_layer_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                            vp, vp, vp, vp, sz, vp]
         L.moe_prefill_workspace_bytes.argtypes = [dp, i32, ctypes.POINTER(sz)]
-        L.moe_draft_prefill_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), i32,
+        L.moe_draft_prefill_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                              vp, vp, vp, vp, sz, vp]
         L.moe_expert_union.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_verify_layer_bf16.argtypes = [vp, dp, vp, vp, vp, vp, sz, vp, vp, i32, i32,
@@ -208,11 +208,11 @@ class Context:
             workspace.numel() * workspace.element_size(), _stream(stream)), "moe_draft_layer_int4")
 
     def draft_prefill_int4(self, desc, x, w_router, router_bias, q_blob, sz_blob, stride_q, stride_sz,
-                           T, y_f32, ids_out, conf_out, workspace, stream=None, symmetric=False):
+                           shared_bf16, T, y_f32, ids_out, conf_out, workspace, stream=None, symmetric=False):
         ex = Int4Experts(q_blob.data_ptr(), sz_blob.data_ptr(), stride_q, stride_sz, int(bool(symmetric)))
         self._check(self._lib.moe_draft_prefill_int4(
             self._h, ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), ctypes.byref(ex),
-            T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _ptr(workspace),
+            _ptr(shared_bf16), T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)), "moe_draft_prefill_int4")
 
     def expert_union(self, ids, n_ids, n_experts, slot_of_expert, mask, lst, n_list, missing,

@@ -319,7 +319,9 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
 
 // workspace of a prefill call: routing weights and sorted assignment indices [T k], the item
 // count (one 256-byte line) and the items
-struct PrefillLayout { size_t w_all, sorted, n_items, items, total; int max_items; };
+// With shared experts: two plans (full chunk, ragged last chunk) and the buffers of one chunk of
+// `chunk` tokens through the bf16 kernels.
+struct PrefillLayout { size_t w_all, sorted, n_items, items, plan_full, plan_tail, shared_ws, total; int max_items, chunk; };
 static PrefillLayout prefill_layout(const moe_layer_desc &d, int T)
 {
     PrefillLayout L;
@@ -331,13 +333,20 @@ static PrefillLayout prefill_layout(const moe_layer_desc &d, int T)
     L.sorted = o;  o += align256(n * 4);
     L.n_items = o; o += 256;
     L.items = o;   o += align256((size_t)L.max_items * sizeof(PrefillItem));
+    L.chunk = MOE_MAX_ASSIGN / d.top_k < MOE_MAX_TOKENS ? MOE_MAX_ASSIGN / d.top_k : MOE_MAX_TOKENS;
+    L.plan_full = L.plan_tail = L.shared_ws = o;
+    if (d.n_shared > 0) {
+        L.plan_full = o; o += align256(sizeof(Plan));
+        L.plan_tail = o; o += align256(sizeof(Plan));
+        L.shared_ws = o; o += ws_layout(d, L.chunk).total;
+    }
     L.total = o;
     return L;
 }
 
 static int check_prefill(const moe_layer_desc *d, int T)
 {
-    if (check_desc(d) != MOE_OK || d->n_shared != 0) return MOE_ERR_INVALID_ARG;
+    if (check_desc(d) != MOE_OK) return MOE_ERR_INVALID_ARG;
     if (T < 1 || T > MOE_MAX_PREFILL_TOKENS) return MOE_ERR_INVALID_ARG;
     return MOE_OK;
 }
@@ -351,7 +360,7 @@ int moe_prefill_workspace_bytes(const moe_layer_desc *desc, int T, size_t *bytes
 
 int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
                            const void *x, const void *wr, const float *bias,
-                           const moe_int4_experts *routed, int T,
+                           const moe_int4_experts *routed, const void *shared, int T,
                            float *y, int32_t *ids_out, float *conf_out,
                            void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -360,8 +369,9 @@ int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         return MOE_ERR_INVALID_ARG;
     if (!aligned(x, 16) || !aligned(wr, 16) || !aligned(bias, 4) || !aligned(routed->q, 16) ||
         !aligned(routed->sz, 16) || routed->expert_stride_q % 16 || routed->expert_stride_sz % 16 ||
-        !aligned(y, 16) || !aligned(ids_out, 4) || !aligned(conf_out, 4))
+        !aligned(y, 16) || !aligned(ids_out, 4) || !aligned(conf_out, 4) || !aligned(shared, 16))
         return MOE_ERR_INVALID_ARG;
+    if (desc->n_shared > 0 && !shared) return MOE_ERR_INVALID_ARG;
     const size_t sz_bytes = routed->symmetric ? moe_int4_expert_scale_bytes(desc) : moe_int4_expert_sz_bytes(desc);
     if (sz_bytes == 0 || routed->expert_stride_q < moe_int4_expert_q_bytes(desc) ||
         routed->expert_stride_sz < sz_bytes)
@@ -388,6 +398,30 @@ int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
     a.items = items; a.n_items = n_items; a.sorted = sorted; a.w_all = w_all;
     { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_prerouted(s, a, L.max_items, st); }
+    if (s.S > 0) {
+        // shared experts stay 16-bit (section 3.4.2): chunks of tokens through the bf16 kernels,
+        // added to y; the intermediate keeps a bf16 remainder as in the draft call
+        const size_t bf16_bytes = moe_bf16_expert_bytes(desc);
+        const WsLayout W = ws_layout(*desc, L.chunk);
+        char *sw = ws + L.shared_ws;
+        Shape sc = s;
+        sc.T = L.chunk;
+        Plan *full = (Plan *)(ws + L.plan_full), *tail = (Plan *)(ws + L.plan_tail);
+        if (T >= L.chunk) launch_shared_plan(sc, full, shared, bf16_bytes, st);
+        for (int t0 = 0; t0 < T; t0 += L.chunk) {
+            const int tc = T - t0 < L.chunk ? T - t0 : L.chunk;
+            sc.T = tc;
+            Plan *plan = full;
+            if (tc < L.chunk) { plan = tail; launch_shared_plan(sc, tail, shared, bf16_bytes, st); }
+            const char *xc = (const char *)x + (size_t)t0 * s.H * 2;
+            { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st);
+              launch_bf16_gateup(sc, plan, 0, s.S, xc, sw + W.hb, sw + W.hb_lo, st); }
+            { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);
+              launch_bf16_down(sc, plan, 0, s.S, sw + W.hb, sw + W.hb_lo, (float *)(sw + W.obuf), st); }
+            { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
+              launch_combine(sc, plan, nullptr, 0, (const float *)(sw + W.obuf), 1, 0, y + (size_t)t0 * s.H, st); }
+        }
+    }
     return hip_status(ctx, hipGetLastError());
 }
 

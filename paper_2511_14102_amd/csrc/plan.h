@@ -91,6 +91,8 @@ void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st);
 // router + plan in one launch; arrivals: 4-byte counter in the workspace, zero between launches
 void launch_route_plan(const Shape &s, const void *x, const void *wr, const float *bias, const PlanArgs &a,
                        uint32_t *arrivals, hipStream_t st);
+// plan of the S shared experts alone over s.T tokens
+void launch_shared_plan(const Shape &s, Plan *plan, const void *shared, size_t shared_stride, hipStream_t st);
 struct PrefillItem;
 void launch_prefill_plan(const int32_t *ids, int n, int E, int32_t *sorted, PrefillItem *items,
                          int32_t *n_items, hipStream_t st);

@@ -217,6 +217,29 @@ void prefill_plan_kernel(const int32_t *__restrict__ ids, int n, int E, int chun
     }
 }
 
+// Plan that runs only the S shared experts over T tokens (rows n .. n + S T, n = T k routed rows
+// that stay dead): what the draft kernel leaves for the shared-expert kernels, for callers that
+// route elsewhere.
+__global__ __launch_bounds__(256)
+void shared_plan_kernel(Plan *__restrict__ p, int T, int k, int S, int E, const char *shared, size_t shared_stride)
+{
+    const int n = T * k, tid = threadIdx.x;
+    for (int i = tid; i < n; i += 256) { p->perm[i] = i; p->row_live[i] = 0; }
+    for (int i = tid; i < S * T; i += 256) {
+        p->row_tok[n + i] = i % T;
+        p->row_w[n + i] = 1.f;
+        p->row_live[n + i] = 1;
+    }
+    if (tid < S) {
+        p->act_expert[tid] = E + tid;
+        p->act_off[tid] = n + tid * T;
+        p->act_cnt[tid] = T;
+        p->act_w0[tid] = (uint64_t)(shared + (size_t)tid * shared_stride);
+        p->act_w1[tid] = 0;
+    }
+    if (tid == 0) { p->n_active = S; p->n_routed_active = 0; p->n_rows = n + S * T; p->n_missing = 0; }
+}
+
 // Builds the execution plan: histogram / permutation, the list of experts to run (shared
 // experts at active indices [0, S), then present routed experts ascending), their weight
 // pointers and row ranges, the per-row token / weight / live flags, and the missing list.
@@ -424,6 +447,11 @@ void launch_route_plan(const Shape &s, const void *x, const void *wr, const floa
 {
     launch(route_plan_kernel, dim3(s.T), dim3(kRouteThreads), 0, st, (const uint16_t *)x, (const uint16_t *)wr,
            bias, s.H, s.renorm, plan_kernel_args(s, a), arrivals);
+}
+
+void launch_shared_plan(const Shape &s, Plan *plan, const void *shared, size_t shared_stride, hipStream_t st)
+{
+    launch(shared_plan_kernel, dim3(1), dim3(256), 0, st, plan, s.T, s.k, s.S, s.E, (const char *)shared, shared_stride);
 }
 
 void launch_prefill_plan(const int32_t *ids, int n, int E, int32_t *sorted, PrefillItem *items,

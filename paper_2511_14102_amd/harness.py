@@ -122,7 +122,7 @@ class DeviceLayer:
         if getattr(self, "_prefill_ws", None) is None or self._prefill_ws.numel() < need:
             self._prefill_ws = torch.empty(need, dtype=torch.uint8, device=dev)
         self.ctx.draft_prefill_int4(self.desc, x, self.router, self.bias, self.q_blob, self.sz_blob,
-                                    self.q_bytes, self.sz_bytes, T, y, ids, conf, self._prefill_ws,
+                                    self.q_bytes, self.sz_bytes, self.shared, T, y, ids, conf, self._prefill_ws,
                                     stream, symmetric=self.symmetric)
         return dict(y=y, ids=ids, conf=conf)
 
