@@ -182,7 +182,12 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     __shared__ int32_t s_row_a[MT];             // assignment index of each row (token) of this item
     __shared__ int32_t s_cnt;
     __shared__ int32_t s_flag;
-    __shared__ float s_red[kWaves][4][NI][NC * 16];   // [wave][row block][token in lane group][lane]
+    // partial gate/up sums [wave][row block][token in lane group][lane].  With 8 tokens the array
+    // (16 KiB) takes the place of the x copy, which is no longer needed by then: the workgroup's LDS
+    // then stays under half of a compute unit's, so that two workgroups share a unit.
+    constexpr bool kRedOverX = MT >= 8;
+    typedef float red_t[4][NI][NC * 16];
+    __shared__ float s_red_own[kRedOverX ? 1 : kWaves * 4 * NI * NC * 16];
     __shared__ __attribute__((aligned(16))) uint16_t s_hhi[MT][32], s_hlo[MT][32];
     __shared__ float s_hsum[MT];
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];   // x copy, then its group sums
@@ -196,6 +201,8 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     const int xstride = H + 8;                   // bf16 elements per token in LDS (+16 B against bank conflicts)
     uint16_t *s_x = reinterpret_cast<uint16_t *>(s_dyn);
     float *s_xsum = reinterpret_cast<float *>(s_dyn + (size_t)MT * xstride * 2);   // [MT][G]
+    static_assert(!kRedOverX || sizeof(red_t) * kWaves == (size_t)kWaves * 4 * 4 * 32 * 4, "launcher sizes the dynamic LDS for this");
+    red_t *s_red = reinterpret_cast<red_t *>(kRedOverX ? reinterpret_cast<float *>(s_dyn) : s_red_own);
     int pre_expert = -1, pre_cnt = 0;
     if constexpr (PRE) {
         const int item = blockIdx.x / (I / 32);
@@ -618,6 +625,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
             for (int pk = 0; pk < kDPacks; ++pk) dsz[pk] = __builtin_nontemporal_load(dsz_ptr(r0, pk));
         }
+        if constexpr (kRedOverX) __syncthreads();      // every wave has finished reading x
         if constexpr (kOwnGu) {
             s_red[wave][c][0][r] = tot1;
         } else if (c < NC) {
@@ -853,8 +861,10 @@ void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st, int m
 {
     const int maxu = PRE ? max_items : (a.E < a.T * a.k ? a.E : a.T * a.k);
     const dim3 grid(maxu * (a.I / 32)), block(kThreads);
-    // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums
-    const size_t lds = (size_t)MT * (a.H + 8) * 2 + (size_t)MT * (a.H / a.g) * 4;
+    // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums; with 8 tokens the
+    // partial gate/up sums (8 waves x 4 row blocks x 4 x 32 floats) later take the same place
+    size_t lds = (size_t)MT * (a.H + 8) * 2 + (size_t)MT * (a.H / a.g) * 4;
+    if (MT >= 8 && lds < (size_t)kWaves * 4 * 4 * 32 * 4) lds = (size_t)kWaves * 4 * 4 * 32 * 4;
     if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM, PRE>, grid, block, lds, st, x, a);
     else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM, PRE>, grid, block, lds, st, x, a);
     else launch_with_lds(draft_fused_kernel<MT, 4, SYM, PRE>, grid, block, lds, st, x, a);

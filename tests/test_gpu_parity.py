@@ -434,6 +434,19 @@ def test_graph_replays_match_eager_calls(ctx, tiny):
         assert np.array_equal(to_np(got[1]), ref["ids"]) and rel_err(to_np(got[0]), ref["y"]) <= TOL_DRAFT
 
 
+def test_eight_tokens_on_a_small_hidden_size(ctx, tiny):
+    # with 5 to 8 tokens the partial gate/up sums reuse the LDS of the x copy, which is smaller than
+    # they are when H is small: the launch must size the buffer for both
+    cfg, D = tiny.cfg, tiny.D
+    for T in (5, 8):
+        x = tokens_with_clear_routing(cfg, tiny.A, T, step=500 + T)
+        ref = oracle_draft(tiny.A, x)
+        r = D.draft(x.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref["ids"])
+        assert rel_err(to_np(r["y"]), ref["y"]) <= TOL_DRAFT
+
+
 def test_mixed_token_counts_share_one_workspace(ctx, tiny):
     """Draft and verify calls of changing token counts on one layer / one workspace: the counters
     the kernels leave in the workspace (tickets, arrivals, tagged slots) must be back in their idle
