@@ -144,6 +144,17 @@ def test_draft_layer_symmetric_format(ctx, name):
             torch.cuda.synchronize()
             assert torch.equal(r["ids"], r2["ids"])
             assert rel_err(to_np(r2["y"]), to_np(r["y"])) <= 1e-5
+    if name in ("tiny", "dsv2lite"):    # the prefill form reads the same scale blobs
+        Tp = 37 if name == "tiny" else 20
+        xp = tokens_with_clear_routing(cfg, A, Tp, step=21, kind="iid")
+        refp = oracle_draft(A, xp)
+        say("prefill (symmetric)", cfg.name, "T", Tp)
+        rp = D.prefill(xp.cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(rp["ids"]), refp["ids"])
+        e = rel_err(to_np(rp["y"]), refp["y"])
+        say("   rel err %.3e" % e)
+        assert e <= TOL_DRAFT
     del D, D2
     gc.collect()
     torch.cuda.empty_cache()
