@@ -366,11 +366,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     }
     __syncthreads();
     const bool ok = PRE || s_flag != 0;
-    // This workgroup will not look at the slots again: it draws a ticket.  The tickets are
+    // This workgroup will not look at the slots again: it will draw a ticket.  The tickets are
     // two-level (kTicketGroups first-level counters, then one) so that the returning atomics do
-    // not queue up on one address, and the atomic is issued by the last wave only after its
-    // first loads are in flight: memory results return in order, so a slow ticket would
-    // otherwise hold back that wave's weight loads (measured: up to 5 us with one counter).
+    // not queue up on one address (measured: up to 5 us with one counter).  The compiler turns the
+    // atomic (one lane, wave-uniform address) into a form whose result it reads back at once, which
+    // waits for everything the drawing wave has in flight.  Where that happens matters: before a
+    // barrier the whole workgroup would wait for it, so the ticket is drawn behind the barriers of
+    // the item set-up (measured on the phi shape: 25.3 us there, 26.3 right after the first loads,
+    // 26.9 before the barrier that ends the gate/up phase; 25.8 and 26.2 with the wait deferred to
+    // the kernel's end, when the loads behind the ticket wait for it in the return queue instead).
     uint32_t ticket = 0xffffffffu;
     auto draw_ticket = [&]() {
         if (!PRE && tid == kThreads - 64)
@@ -394,6 +398,109 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
     expert = __builtin_amdgcn_readfirstlane(expert);   // the same in every lane; tell the compiler
+    // ---- 3a. the first window of weight loads goes out before anything else of the item is set
+    // up: the addresses need only the expert and the slice, and every microsecond of bookkeeping
+    // behind them is hidden by their latency.  (Without an expert -- a surplus workgroup -- the
+    // addresses are those of expert 0 and the loaded tiles are not used.)
+    const int ex = expert >= 0 ? expert : 0;
+    const int U = H / 32;
+    const int r = lane & 15, c = lane >> 4;                  // MFMA lane coordinates
+    const UnpackConsts uk = unpack_consts();
+    const char *qb = a.q + (size_t)ex * a.stride_q;
+    const char *szb = a.sz + (size_t)ex * a.stride_sz;
+    // codes: [gate|up tiles (slice, ku)] then [down tiles (slice, rt)], 64 lanes x 16 B each
+    // A tile's address is a wave-uniform base (scalar arithmetic) plus the lane's 16 bytes.
+    const int gu0 = slice * U, dn0 = nslice * U + slice * (H / 64);          // first tile of each part
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    auto tile_ptr = [&](int tile) {
+        return reinterpret_cast<const u32x4 *>(qb + (size_t)tile * 1024 + lane_off);
+    };
+    // scale/zero: 16 B = the 4 row blocks' (s, z) of lane row r; [gate|up (slice, group)] then
+    // [down (group of I, rt)]
+    // (symmetric format: 16 B = the 4 row blocks' s of row r for two groups / two row tiles)
+    constexpr int kEpl = SYM ? 2 : 1;                        // groups (row tiles) per 16-byte load
+    const u32x4 *szgu = reinterpret_cast<const u32x4 *>(szb) + (size_t)slice * (G / kEpl) * 16 + r;
+    const u32x4 *szd = reinterpret_cast<const u32x4 *>(szb) + (size_t)nslice * (G / kEpl) * 16 +
+                       (size_t)((slice * 32) / g) * (H / (64 * kEpl)) * 16 + r;
+
+    // ---- this wave's tile stream: its gate/up tiles u0 .. u1 (K = H split over the waves by
+    // groups), padded to whole windows, then its down row tiles wave, wave + 8, ... (their loads
+    // do not depend on h).  A rolling window of kGuWin tiles is in flight.  EVERY load of the
+    // stream is unconditional: past the end of a part its address is clamped to the part's
+    // last tile.  The compiler counts the loads in flight in program order; a load under a
+    // branch makes it wait for all of them wherever it needs one, which empties the window.
+    const int nrt = H / 64;
+    // (the symmetric format shares a load between two groups / row tiles: whole pairs per wave)
+    const int u0 = ((wave * (G / kEpl)) / kWaves) * kEpl * UPG, u1 = (((wave + 1) * (G / kEpl)) / kWaves) * kEpl * UPG;
+    const int nt = u1 - u0;
+    const int ntp = (nt + kGuWin - 1) / kGuWin * kGuWin;
+    const int r0 = ((wave * (nrt / kEpl)) / kWaves) * kEpl, r1 = (((wave + 1) * (nrt / kEpl)) / kWaves) * kEpl;   // this wave's down row tiles
+    const int rt_last = r1 > r0 ? r1 - 1 : 0;
+    const int g_last = nt > 0 ? (u1 - 1) / UPG : 0;
+    auto stream_ptr = [&](int p) -> const u32x4 * {            // p: position in the stream
+        const int ku = u0 + p;
+        const int rt = r0 + (p - ntp);
+        const int gt = gu0 + (ku < u1 ? ku : u1 - 1);
+        const int dt = dn0 + (rt < r1 ? rt : rt_last);
+        return tile_ptr(p < ntp ? gt : dt);
+    };
+    // Scale/zero entries are fetched 4 kEpl groups (or row tiles) per load: lane group c
+    // takes the 16 bytes of row r of load unit first / kEpl + 4 pk + c, and a lane picks the
+    // entry of the group at hand from that lane group with a lane permute.  `first` is a
+    // multiple of kEpl everywhere below.
+    constexpr int kPerPack = 4 * kEpl;
+    constexpr int kSzPacks = (kSzWin + kPerPack - 1) / kPerPack;
+    auto gsz_ptr = [&](int first, int pk) {
+        const int gi = first / kEpl + 4 * pk + c;
+        const int last = g_last / kEpl;
+        return szgu + (size_t)(gi < last ? gi : last) * 16;
+    };
+    // parameters of the j-th group (row tile) after the packs' first one, lane row r
+    auto pick = [&](const u32x4 *packs, int j) {
+        const u32x4 &v = packs[j / kPerPack];
+        const int src = ((j / kEpl) % 4) * 16 + r;
+        GroupParams<SYM> p;
+        if constexpr (SYM) {
+            p.w[0] = (uint32_t)__shfl((int)((j & 1) ? v.z : v.x), src, 64);
+            p.w[1] = (uint32_t)__shfl((int)((j & 1) ? v.w : v.y), src, 64);
+        } else {
+            p.w[0] = (uint32_t)__shfl((int)v.x, src, 64);
+            p.w[1] = (uint32_t)__shfl((int)v.y, src, 64);
+            p.w[2] = (uint32_t)__shfl((int)v.z, src, 64);
+            p.w[3] = (uint32_t)__shfl((int)v.w, src, 64);
+        }
+        return p;
+    };
+    // With ONE token all 16 A rows hold that token, so every lane group ends up with the same
+    // sums.  Lane group c then finishes row block c only: it loads that block's entry itself
+    // (no lane permutes), picks accumulator c and applies scale and zero to one value instead
+    // of four.
+    constexpr bool kOwnGu = MT == 1;
+    using gentry_t = typename std::conditional<SYM, uint16_t, uint32_t>::type;
+    const gentry_t *gent_base = reinterpret_cast<const gentry_t *>(szb) + (size_t)slice * G * 64 +
+                                (SYM ? r * 8 : r * 4) + c;
+    auto gent_load = [&](int gi) -> uint32_t {
+        const int t = gi < g_last ? gi : g_last;
+        return (uint32_t)__builtin_nontemporal_load(gent_base + (SYM ? (t >> 1) * 128 + (t & 1) * 4 : t * 64));
+    };
+    const uint32_t cm1 = 0u - (uint32_t)(c & 1), cm2 = 0u - (uint32_t)(c >> 1);
+    auto of_my_block = [&](float v0, float v1, float v2, float v3) {   // v_c, chosen with bit masks
+        const uint32_t lo = (__float_as_uint(v1) & cm1) | (__float_as_uint(v0) & ~cm1);
+        const uint32_t hi = (__float_as_uint(v3) & cm1) | (__float_as_uint(v2) & ~cm1);
+        return __uint_as_float((hi & cm2) | (lo & ~cm2));
+    };
+    u32x4 win[kGuWin], gsz[kSzPacks];
+    uint32_t gent[kSzWin] = {};
+#pragma unroll
+    for (int i = 0; i < kGuWin; ++i) win[i] = __builtin_nontemporal_load(stream_ptr(i));
+    if constexpr (kOwnGu) {
+#pragma unroll
+        for (int j = 0; j < kSzWin; ++j) gent[j] = gent_load(u0 / UPG + j);
+    } else {
+#pragma unroll
+        for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG, pk));
+    }
+    // ---- 3b. the rows (tokens) of the item
     if (tid == 0) s_cnt = pre_cnt;
     if (tid < MT) s_hsum[tid] = 0.f;
     __syncthreads();
@@ -413,28 +520,9 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     }
     __syncthreads();
     const int cnt = __builtin_amdgcn_readfirstlane(s_cnt);
+    draw_ticket();
 
     if (expert >= 0 && cnt > 0) {
-        const int U = H / 32;
-        const int r = lane & 15, c = lane >> 4;                  // MFMA lane coordinates
-        const UnpackConsts uk = unpack_consts();
-        const char *qb = a.q + (size_t)expert * a.stride_q;
-        const char *szb = a.sz + (size_t)expert * a.stride_sz;
-        // codes: [gate|up tiles (slice, ku)] then [down tiles (slice, rt)], 64 lanes x 16 B each
-        // A tile's address is a wave-uniform base (scalar arithmetic) plus the lane's 16 bytes.
-        const int gu0 = slice * U, dn0 = nslice * U + slice * (H / 64);          // first tile of each part
-        const uint32_t lane_off = (uint32_t)lane * 16u;
-        auto tile_ptr = [&](int tile) {
-            return reinterpret_cast<const u32x4 *>(qb + (size_t)tile * 1024 + lane_off);
-        };
-        // scale/zero: 16 B = the 4 row blocks' (s, z) of lane row r; [gate|up (slice, group)] then
-        // [down (group of I, rt)]
-        // (symmetric format: 16 B = the 4 row blocks' s of row r for two groups / two row tiles)
-        constexpr int kEpl = SYM ? 2 : 1;                        // groups (row tiles) per 16-byte load
-        const u32x4 *szgu = reinterpret_cast<const u32x4 *>(szb) + (size_t)slice * (G / kEpl) * 16 + r;
-        const u32x4 *szd = reinterpret_cast<const u32x4 *>(szb) + (size_t)nslice * (G / kEpl) * 16 +
-                           (size_t)((slice * 32) / g) * (H / (64 * kEpl)) * 16 + r;
-
         // A-operand row of this lane: token slot r (slots >= cnt repeat slot 0; their D rows are ignored)
         auto lds_row = [&](int slot) { return PRE ? slot : s_row_a[slot] / k; };   // where the slot's x was staged
         const uint16_t *xrow = s_x + lds_row(r < cnt ? r : 0) * xstride + c * 8;
@@ -446,54 +534,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             tok[i] = lds_row(slot < cnt ? slot : 0);
         }
 
-        // ---- this wave's tile stream: its gate/up tiles u0 .. u1 (K = H split over the waves by
-        // groups), padded to whole windows, then its down row tiles wave, wave + 8, ... (their loads
-        // do not depend on h).  A rolling window of kGuWin tiles is in flight.  EVERY load of the
-        // stream is unconditional: past the end of a part its address is clamped to the part's
-        // last tile.  The compiler counts the loads in flight in program order; a load under a
-        // branch makes it wait for all of them wherever it needs one, which empties the window.
-        const int nrt = H / 64;
-        // (the symmetric format shares a load between two groups / row tiles: whole pairs per wave)
-        const int u0 = ((wave * (G / kEpl)) / kWaves) * kEpl * UPG, u1 = (((wave + 1) * (G / kEpl)) / kWaves) * kEpl * UPG;
-        const int nt = u1 - u0;
-        const int ntp = (nt + kGuWin - 1) / kGuWin * kGuWin;
-        const int r0 = ((wave * (nrt / kEpl)) / kWaves) * kEpl, r1 = (((wave + 1) * (nrt / kEpl)) / kWaves) * kEpl;   // this wave's down row tiles
-        const int rt_last = r1 > r0 ? r1 - 1 : 0;
-        const int g_last = nt > 0 ? (u1 - 1) / UPG : 0;
-        auto stream_ptr = [&](int p) -> const u32x4 * {            // p: position in the stream
-            const int ku = u0 + p;
-            const int rt = r0 + (p - ntp);
-            const int gt = gu0 + (ku < u1 ? ku : u1 - 1);
-            const int dt = dn0 + (rt < r1 ? rt : rt_last);
-            return tile_ptr(p < ntp ? gt : dt);
-        };
-        // Scale/zero entries are fetched 4 kEpl groups (or row tiles) per load: lane group c
-        // takes the 16 bytes of row r of load unit first / kEpl + 4 pk + c, and a lane picks the
-        // entry of the group at hand from that lane group with a lane permute.  `first` is a
-        // multiple of kEpl everywhere below.
-        constexpr int kPerPack = 4 * kEpl;
-        constexpr int kSzPacks = (kSzWin + kPerPack - 1) / kPerPack;
-        auto gsz_ptr = [&](int first, int pk) {
-            const int gi = first / kEpl + 4 * pk + c;
-            const int last = g_last / kEpl;
-            return szgu + (size_t)(gi < last ? gi : last) * 16;
-        };
-        // parameters of the j-th group (row tile) after the packs' first one, lane row r
-        auto pick = [&](const u32x4 *packs, int j) {
-            const u32x4 &v = packs[j / kPerPack];
-            const int src = ((j / kEpl) % 4) * 16 + r;
-            GroupParams<SYM> p;
-            if constexpr (SYM) {
-                p.w[0] = (uint32_t)__shfl((int)((j & 1) ? v.z : v.x), src, 64);
-                p.w[1] = (uint32_t)__shfl((int)((j & 1) ? v.w : v.y), src, 64);
-            } else {
-                p.w[0] = (uint32_t)__shfl((int)v.x, src, 64);
-                p.w[1] = (uint32_t)__shfl((int)v.y, src, 64);
-                p.w[2] = (uint32_t)__shfl((int)v.z, src, 64);
-                p.w[3] = (uint32_t)__shfl((int)v.w, src, 64);
-            }
-            return p;
-        };
         float tot[4][NI];
         f32x4 acc[4];
 #pragma unroll
@@ -502,37 +542,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
             for (int i = 0; i < NI; ++i) tot[d][i] = 0.f;
         }
-        // With ONE token all 16 A rows hold that token, so every lane group ends up with the same
-        // sums.  Lane group c then finishes row block c only: it loads that block's entry itself
-        // (no lane permutes), picks accumulator c and applies scale and zero to one value instead
-        // of four.
-        constexpr bool kOwnGu = MT == 1;
-        using gentry_t = typename std::conditional<SYM, uint16_t, uint32_t>::type;
-        const gentry_t *gent_base = reinterpret_cast<const gentry_t *>(szb) + (size_t)slice * G * 64 +
-                                    (SYM ? r * 8 : r * 4) + c;
-        auto gent_load = [&](int gi) -> uint32_t {
-            const int t = gi < g_last ? gi : g_last;
-            return (uint32_t)__builtin_nontemporal_load(gent_base + (SYM ? (t >> 1) * 128 + (t & 1) * 4 : t * 64));
-        };
-        const uint32_t cm1 = 0u - (uint32_t)(c & 1), cm2 = 0u - (uint32_t)(c >> 1);
-        auto of_my_block = [&](float v0, float v1, float v2, float v3) {   // v_c, chosen with bit masks
-            const uint32_t lo = (__float_as_uint(v1) & cm1) | (__float_as_uint(v0) & ~cm1);
-            const uint32_t hi = (__float_as_uint(v3) & cm1) | (__float_as_uint(v2) & ~cm1);
-            return __uint_as_float((hi & cm2) | (lo & ~cm2));
-        };
         float tot1 = 0.f;
-        u32x4 win[kGuWin], gsz[kSzPacks];
-        uint32_t gent[kSzWin] = {};
-#pragma unroll
-        for (int i = 0; i < kGuWin; ++i) win[i] = __builtin_nontemporal_load(stream_ptr(i));
-        if constexpr (kOwnGu) {
-#pragma unroll
-            for (int j = 0; j < kSzWin; ++j) gent[j] = gent_load(u0 / UPG + j);
-        } else {
-#pragma unroll
-            for (int pk = 0; pk < kSzPacks; ++pk) gsz[pk] = __builtin_nontemporal_load(gsz_ptr(u0 / UPG, pk));
-        }
-        draw_ticket();
         u32x4 xa = *reinterpret_cast<const u32x4 *>(xrow + (nt > 0 ? u0 : 0) * 32);
         // one window of the gate/up part; kGuard: some of its tiles may lie past the wave's run (the
         // padding of the last window) and are skipped.  Full windows carry no per-tile tests.
@@ -754,9 +764,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         down_pass(j0, std::false_type{});
     }
 
-    else {
-        draw_ticket();
-    }
     if constexpr (PRE) return;
     // ---- 4. last ticket: every workgroup has its logits, put the workspace back to idle
     if (tid == kThreads - 64) {
