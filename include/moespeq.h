@@ -27,7 +27,9 @@
  * size, S shared experts.  Assignment index a = t * k + j (token-major, j = rank).
  * Limits: 1 <= T <= MOE_MAX_TOKENS (draft: MOE_MAX_DRAFT_TOKENS), E <= MOE_MAX_EXPERTS,
  * k <= min(E, MOE_MAX_TOPK), T * k <= MOE_MAX_ASSIGN, S <= MOE_MAX_SHARED, H and I multiples
- * of 64, g in {32, 64, 128} dividing both H and I.
+ * of 64, g in {32, 64, 128} dividing both H and I.  A draft call keeps a copy of its tokens in
+ * LDS: T * (2 H + 16 + 4 H / g) bytes, T rounded up to 1, 2, 4 or 8, must stay under 140 KiB
+ * (H <= 8192 for 8 tokens and for the prefill call, <= 16384 for 4), else MOE_ERR_INVALID_ARG.
  *
  * Kernel-native weight layouts (part of the ABI; pack.py builds them from row-major arrays)
  *

@@ -287,10 +287,11 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         routed->expert_stride_sz < sz_bytes)
         return MOE_ERR_INVALID_ARG;
     if (desc->n_shared > 0 && !shared) return MOE_ERR_INVALID_ARG;
+    const Shape s = make_shape(desc, T);
+    if (!draft_fits(s, T)) return MOE_ERR_INVALID_ARG;     // hidden size too large for T tokens per call
     const WsLayout L = ws_layout(*desc, T);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
 
-    const Shape s = make_shape(desc, T);
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     Plan *plan = (Plan *)(ws + L.plan);
@@ -376,10 +377,11 @@ int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     if (sz_bytes == 0 || routed->expert_stride_q < moe_int4_expert_q_bytes(desc) ||
         routed->expert_stride_sz < sz_bytes)
         return MOE_ERR_INVALID_ARG;
+    const Shape s = make_shape(desc, T);
+    if (!draft_fits(s, kPrefillChunk)) return MOE_ERR_INVALID_ARG;
     const PrefillLayout L = prefill_layout(*desc, T);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
 
-    const Shape s = make_shape(desc, T);
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     float *w_all = (float *)(ws + L.w_all);

@@ -863,15 +863,21 @@ void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st
     launch(kernel, grid, block, lds, st, x, a);
 }
 
+// dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums; with 8 tokens the
+// partial gate/up sums (8 waves x 4 row blocks x 4 x 32 floats) later take the same place
+size_t draft_dynamic_lds(int MT, int H, int g)
+{
+    size_t lds = (size_t)MT * (H + 8) * 2 + (size_t)MT * (H / g) * 4;
+    if (MT >= 8 && lds < (size_t)kWaves * 4 * 4 * 32 * 4) lds = (size_t)kWaves * 4 * 4 * 32 * 4;
+    return lds;
+}
+
 template <int MT, bool SYM, bool PRE = false>
 void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st, int max_items = 0)
 {
     const int maxu = PRE ? max_items : (a.E < a.T * a.k ? a.E : a.T * a.k);
     const dim3 grid(maxu * (a.I / 32)), block(kThreads);
-    // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums; with 8 tokens the
-    // partial gate/up sums (8 waves x 4 row blocks x 4 x 32 floats) later take the same place
-    size_t lds = (size_t)MT * (a.H + 8) * 2 + (size_t)MT * (a.H / a.g) * 4;
-    if (MT >= 8 && lds < (size_t)kWaves * 4 * 4 * 32 * 4) lds = (size_t)kWaves * 4 * 4 * 32 * 4;
+    const size_t lds = draft_dynamic_lds(MT, a.H, a.g);
     if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM, PRE>, grid, block, lds, st, x, a);
     else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM, PRE>, grid, block, lds, st, x, a);
     else launch_with_lds(draft_fused_kernel<MT, 4, SYM, PRE>, grid, block, lds, st, x, a);
@@ -915,6 +921,13 @@ void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &d, int max_ite
     const uint16_t *x = (const uint16_t *)d.x;
     if (d.symmetric) launch_fused_t<kPrefillChunk, true, true>(x, a, st, max_items);
     else launch_fused_t<kPrefillChunk, false, true>(x, a, st, max_items);
+}
+
+bool draft_fits(const Shape &s, int tokens)
+{
+    const int MT = tokens <= 1 ? 1 : (tokens <= 2 ? 2 : (tokens <= 4 ? 4 : 8));
+    // 160 KiB of LDS per workgroup, 20 KiB of them for the kernel's static arrays
+    return draft_dynamic_lds(MT, s.H, s.g) <= (size_t)(160 - 20) * 1024;
 }
 
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st)

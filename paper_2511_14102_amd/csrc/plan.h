@@ -116,6 +116,8 @@ struct DraftFusedArgs {
     const PrefillItem *items; const int32_t *n_items; const int32_t *sorted; const float *w_all;   // prerouted only
 };
 void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
+// whether the x copy of a call with `tokens` tokens per workgroup (1-8) fits into LDS
+bool draft_fits(const Shape &s, int tokens);
 // grid sized for max_items work items; y must have been cleared
 void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &a, int max_items, hipStream_t st);
 void launch_zero(void *p, size_t bytes, hipStream_t st);

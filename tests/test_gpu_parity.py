@@ -384,6 +384,22 @@ def test_argument_errors_enqueue_nothing(ctx, tiny):
     with pytest.raises(B.MoeError) as ei:                  # draft takes at most 8 tokens
         D.draft(torch.zeros((9, 256), dtype=torch.bfloat16, device="cuda"))
     assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    # a hidden size whose token copy does not fit into LDS for 8 tokens (it does for 4): rejected on
+    # the host, nothing is read (the buffers here are far too small for the shape)
+    big = B.LayerDesc(16384, 4, 128, 1, 0, 128, 1)
+    assert B.validate_desc(big) == 0
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(B.workspace_bytes(big, 8), dtype=torch.uint8, device="cuda")
+    for T, what in ((8, "draft"), (19, "prefill")):
+        with pytest.raises(B.MoeError) as ei:
+            if what == "draft":
+                ctx.draft_layer_int4(big, buf, buf, None, buf, buf, B.int4_expert_q_bytes(big),
+                                     B.int4_expert_sz_bytes(big), None, T, buf, buf, None, ws)
+            else:
+                pws = torch.zeros(B.prefill_workspace_bytes(big, T), dtype=torch.uint8, device="cuda")
+                ctx.draft_prefill_int4(big, buf, buf, None, buf, buf, B.int4_expert_q_bytes(big),
+                                       B.int4_expert_sz_bytes(big), None, T, buf, buf, None, pws)
+        assert ei.value.status == B.MOE_ERR_INVALID_ARG, what
     torch.cuda.synchronize()
 
 
