@@ -216,9 +216,9 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * The draft model over a long run of tokens (the prompt; section 3.4.2-3.4.3 describe the same
- * int4 layer, section 3.1 the draft model that has to consume the prompt before it can
- * speculate).  Same mathematics, arguments and outputs as moe_draft_layer_int4 for 1 <= T <=
+ * The draft model over a long run of tokens (the prompt).  Section 3.4.2-3.4.3 describe the
+ * int4 layer and choose its backend for the prefill stage as well as the decode stage (the
+ * figure comparing backends there).  Same mathematics, arguments and outputs as moe_draft_layer_int4 for 1 <= T <=
  * MOE_MAX_PREFILL_TOKENS tokens.  All tokens are routed first, the assignments are grouped by
  * expert, and every expert's weights are streamed once per 8 of its assignments (a
  * token-by-token loop streams them once per assignment); shared experts run over chunks of up
