@@ -17,10 +17,6 @@ namespace {
 
 constexpr int kRouteThreads = 1024;
 
-__device__ inline double bf16_to_f64(uint16_t b) {
-    return (double)__uint_as_float((uint32_t)b << 16);
-}
-
 // One workgroup per token: logits of all experts (one wave per expert row at a time), then
 // wave 0 selects the top k and computes the softmax weights.
 // kAgent: the results are stored at agent scope (another workgroup of the same launch reads them).
@@ -40,6 +36,7 @@ __device__ inline void route_token(const uint16_t *__restrict__ x, const uint16_
                                    int32_t *__restrict__ ids, float *__restrict__ w, float *__restrict__ conf)
 {
     __shared__ double s_logit[MOE_MAX_EXPERTS];
+    __shared__ int32_t s_rank[MOE_MAX_EXPERTS];
     const int t = blockIdx.x;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nwave = kRouteThreads / 64;
@@ -48,7 +45,10 @@ __device__ inline void route_token(const uint16_t *__restrict__ x, const uint16_
 
     for (int e = wave; e < E; e += nwave) {
         const uint16_t *row = wr + (size_t)e * H;
-        double acc = 0.0;
+        // eight independent partial sums instead of one chain of dependent fp64 additions; the
+        // products are exact in fp32 (bf16 x bf16).  (The loop is bound by the instruction rate of
+        // the one compute unit a token's workgroup runs on: batching the loads did not help.)
+        double part[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
         for (int c = lane; c < chunks; c += 64) {
             uint4 xv = *reinterpret_cast<const uint4 *>(xt + c * 8);
             uint4 wv = *reinterpret_cast<const uint4 *>(row + c * 8);
@@ -56,79 +56,57 @@ __device__ inline void route_token(const uint16_t *__restrict__ x, const uint16_
             const uint32_t ws[4] = {wv.x, wv.y, wv.z, wv.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                acc = fma(bf16_to_f64((uint16_t)(xs[i] & 0xffff)), bf16_to_f64((uint16_t)(ws[i] & 0xffff)), acc);
-                acc = fma(bf16_to_f64((uint16_t)(xs[i] >> 16)), bf16_to_f64((uint16_t)(ws[i] >> 16)), acc);
+                part[2 * i] += (double)(__uint_as_float(xs[i] << 16) * __uint_as_float(ws[i] << 16));
+                part[2 * i + 1] += (double)(__uint_as_float(xs[i] & 0xffff0000u) * __uint_as_float(ws[i] & 0xffff0000u));
             }
         }
+        double acc = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
         acc = wave::sum(acc);
-        if (lane == 0) s_logit[e] = acc + (bias ? (double)bias[e] : 0.0);
+        if (lane == 0) { s_logit[e] = acc + (bias ? (double)bias[e] : 0.0); s_rank[e] = 0; }
     }
 
     __syncthreads();
+    // Rank of every logit under (larger first, lower index first among equals), counted by all
+    // sixteen waves, each over its share of the experts (one wave alone needs microseconds for a
+    // serial selection: about 16 clocks per instruction, and the count grows with E).  The order is
+    // strict, so the ranks are a permutation and rank < k is the selection.
+    wave::count_ranks(s_logit, s_rank, E, lane, wave, nwave);
+    __syncthreads();
     if (wave != 0) return;                 // (the caller's next barrier is reached by all waves)
-    if (E <= 64) {
-        // Lane e holds logit e; its rank under (larger first, lower index first among equals) is
-        // counted against every logit read from its lane with a wave-uniform index.  The order
-        // is strict, so the ranks are a permutation and rank < k is the selection.
-        const double mine = lane < E ? s_logit[lane] : -INFINITY;
-        int rank = 0;
-        double mx = -INFINITY;
-        for (int e2 = 0; e2 < E; ++e2) {
-            const double v = wave::from_lane(mine, e2);
-            mx = fmax(mx, v);
-            rank += (v > mine || (v == mine && e2 < lane)) ? 1 : 0;
-        }
-        const double pe = lane < E ? exp(mine - mx) : 0.0;
-        const double p = pe / wave::sum(pe);
-        const bool sel = lane < E && rank < k;
-        const double sel_sum = wave::sum(sel ? p : 0.0);
-        if (sel) {
-            put<kAgent>(&ids[(size_t)t * k + rank], (int32_t)lane);
-            const float c = (float)p;
-            if (conf) put<kAgent>(&conf[(size_t)t * k + rank], c);
-            put<kAgent>(&w[(size_t)t * k + rank], renorm ? (float)(p / sel_sum) : c);
-        }
-        return;
-    }
-    // each lane owns logits lane, lane + 64, lane + 128, lane + 192
-    double l[4];
+    double mine[4], pe[4];
+    int rank[4];
     double mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        int e = lane + 64 * i;
-        l[i] = e < E ? s_logit[e] : -INFINITY;
-        mx = fmax(mx, l[i]);
+        const int e = lane + 64 * i;
+        const bool have = 64 * i < E && e < E;
+        mine[i] = have ? s_logit[e] : -INFINITY;
+        rank[i] = have ? s_rank[e] : MOE_MAX_EXPERTS;
+        mx = fmax(mx, mine[i]);
     }
     mx = wave::max(mx);
-    double den = 0.0;
+    double den = 0.0, sel = 0.0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-        if (lane + 64 * i < E) den += exp(l[i] - mx);
-    den = wave::sum(den);
-
-    unsigned taken = 0;
-    double sel_sum = 0.0;
-    double my_conf = 0.0;      // lane j keeps the j-th confidence
-    int my_id = 0;
-    for (int j = 0; j < k; ++j) {
-        double bv = -INFINITY;
-        int bi = wave::kNone;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int e = lane + 64 * i;
-            if (e < E && !((taken >> i) & 1) && (bi == wave::kNone || l[i] > bv)) { bv = l[i]; bi = e; }
-        }
-        { const wave::Best b = wave::argmax(wave::Best{bv, bi}); bv = b.v; bi = b.i; }
-        if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-        double p = exp(bv - mx) / den;
-        sel_sum += p;
-        if (lane == j) { my_conf = p; my_id = bi; }
+    for (int i = 0; i < 4; ++i) {
+        pe[i] = rank[i] < MOE_MAX_EXPERTS ? exp(mine[i] - mx) : 0.0;
+        den += pe[i];
     }
-    if (lane < k) {
-        put<kAgent>(&ids[(size_t)t * k + lane], (int32_t)my_id);
-        float c = (float)my_conf;
-        if (conf) put<kAgent>(&conf[(size_t)t * k + lane], c);
-        put<kAgent>(&w[(size_t)t * k + lane], renorm ? (float)(my_conf / sel_sum) : c);
+    den = wave::sum(den);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        pe[i] = pe[i] / den;
+        sel += rank[i] < k ? pe[i] : 0.0;
+    }
+    sel = wave::sum(sel);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (rank[i] < k) {
+            const size_t o = (size_t)t * k + rank[i];
+            put<kAgent>(&ids[o], (int32_t)(lane + 64 * i));
+            const float c = (float)pe[i];
+            if (conf) put<kAgent>(&conf[o], c);
+            put<kAgent>(&w[o], renorm ? (float)(pe[i] / sel) : c);
+        }
     }
 }
 
@@ -140,27 +118,61 @@ void route_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ w
     route_token<false>(x, wr, bias, H, E, k, renorm, ids, w, conf);
 }
 
-// count / off / perm for n assignments over E experts; one workgroup, results in `count`,
-// `off`, `perm` (global or shared memory).  Thread e owns expert e.
+// count / off / perm for n <= MOE_MAX_ASSIGN assignments over E experts; one workgroup of at least
+// 256 threads, results in `count`, `off`, `perm` (global or shared memory), `ids` in LDS.
+// Thread a owns assignment a: counts by LDS atomics, offsets by a scan in wave 0 (four experts per
+// lane), and the place of a inside its expert is the number of earlier assignments with the same
+// expert, counted over broadcast reads of ids (ascending a inside an expert: stable).  The loops
+// of the first version (thread e scanning all assignments and all smaller experts, one dependent
+// LDS read per step) took 12 us for 64 assignments over 128 experts.
 __device__ inline void histogram_perm(const int32_t *ids, int n, int E, int32_t *count,
                                       int32_t *off, int32_t *perm, int32_t *s_count)
 {
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        int c = 0;
-        for (int a = 0; a < n; ++a) c += (ids[a] == e);
-        s_count[e] = c;
-        count[e] = c;
+    __shared__ int32_t s_excl[MOE_MAX_EXPERTS + 1];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < E; e += blockDim.x) s_count[e] = 0;
+    __syncthreads();
+    const int my_e = tid < n ? ids[tid] : -1;
+    if (tid < n) atomicAdd(&s_count[my_e], 1);
+    __syncthreads();
+    if (tid < 64) {
+        int c[4], sum = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = 4 * tid + i;
+            c[i] = e < E ? s_count[e] : 0;
+            sum += c[i];
+        }
+        int incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int v = __shfl_up(incl, d, 64);
+            if (tid >= d) incl += v;
+        }
+        int base = incl - sum;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = 4 * tid + i;
+            if (e < E) s_excl[e] = base;
+            base += c[i];
+        }
+        if (tid == 0) s_excl[E] = n;
     }
     __syncthreads();
-    for (int e = threadIdx.x; e <= E; e += blockDim.x) {
-        int o = 0;
-        for (int i = 0; i < e; ++i) o += s_count[i];
-        off[e] = o;
-        if (e < E) {
-            int p = o;
-            for (int a = 0; a < n; ++a)
-                if (ids[a] == e) perm[p++] = a;     // ascending a: stable
+    for (int e = tid; e <= E; e += blockDim.x) {
+        off[e] = s_excl[e];
+        if (e < E) count[e] = s_count[e];
+    }
+    if (tid < n) {
+        int before = 0;
+        for (int a = 0; a < n; a += 8) {
+            int v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = ids[a + j < n ? a + j : n - 1];       // the same address in every lane
+#pragma unroll
+            for (int j = 0; j < 8; ++j) before += (int)(a + j < tid) & (int)(v[j] == my_e);
         }
+        perm[s_excl[my_e] + before] = tid;
     }
     __syncthreads();
 }

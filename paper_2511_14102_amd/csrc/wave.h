@@ -91,5 +91,51 @@ __device__ inline float row_sum(float v) { return row_all(v, [](float a, float b
 
 __device__ inline Best argmax(Best b) { return all(b, [](Best x, Best y) { return better(x, y); }); }
 
+// Rank counting for a top-k selection by several waves.  logit[0 .. E) and rank[0 .. E) live in
+// LDS, rank zeroed.  The calling wave adds to rank[e] the number of logits e2 = first,
+// first + stride, ... that come before logit e in the order (larger first, lower index first
+// among equals); with every e2 covered by some wave, rank[] becomes the position of each logit in
+// that strict order.  Lane l keeps logits l, l + 64, ... (NR of them, NR >= ceil(E / 64)) in
+// registers; the logits e2 are broadcast reads, eight in flight, compared without branches.
+template <int NR>
+__device__ inline void count_ranks(const double *logit, int32_t *rank, int E, int lane, int first, int stride)
+{
+    double mine[NR];
+    int part[NR];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        const int e = lane + 64 * i;
+        mine[i] = logit[e < E ? e : E - 1];
+        part[i] = 0;
+    }
+    for (int e2 = first; e2 < E; e2 += 8 * stride) {
+        double v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int idx = e2 + j * stride;
+            v[j] = logit[idx < E ? idx : E - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int idx = e2 + j * stride;
+            const int live = idx < E ? 1 : 0;
+#pragma unroll
+            for (int i = 0; i < NR; ++i)
+                part[i] += live & ((int)(v[j] > mine[i]) | ((int)(v[j] == mine[i]) & (int)(idx < lane + 64 * i)));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+        const int e = lane + 64 * i;
+        if (e < E && part[i] != 0) atomicAdd(&rank[e], part[i]);
+    }
+}
+__device__ inline void count_ranks(const double *logit, int32_t *rank, int E, int lane, int first, int stride)
+{
+    if (E <= 64) count_ranks<1>(logit, rank, E, lane, first, stride);
+    else if (E <= 128) count_ranks<2>(logit, rank, E, lane, first, stride);
+    else count_ranks<4>(logit, rank, E, lane, first, stride);
+}
+
 }  // namespace wave
 }  // namespace moespeq
