@@ -17,8 +17,9 @@ namespace {
 
 constexpr int kRouteThreads = 1024;
 
-// One workgroup per token: logits of all experts (one wave per expert row at a time), then
-// wave 0 selects the top k and computes the softmax weights.
+// One workgroup per token: logits of all experts (one wave per expert row at a time), ranks of
+// the logits counted by all waves, then wave 0 writes the k selected experts in rank order with
+// their softmax weights.
 // kAgent: the results are stored at agent scope (another workgroup of the same launch reads them).
 template <bool kAgent, typename V>
 __device__ inline void put(V *p, V v) {
