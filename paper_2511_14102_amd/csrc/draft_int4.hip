@@ -203,6 +203,10 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     float *s_xsum = reinterpret_cast<float *>(s_dyn + (size_t)MT * xstride * 2);   // [MT][G]
     static_assert(!kRedOverX || sizeof(red_t) * kWaves == (size_t)kWaves * 4 * 4 * 32 * 4, "launcher sizes the dynamic LDS for this");
     red_t *s_red = reinterpret_cast<red_t *>(kRedOverX ? reinterpret_cast<float *>(s_dyn) : s_red_own);
+    // routing scratch behind the group sums, used with more than 64 experts: logits [MT][E] (fp64), ranks
+    const size_t logit_off = ((size_t)MT * xstride * 2 + (size_t)MT * G * 4 + 7) & ~(size_t)7;
+    double *s_logit = reinterpret_cast<double *>(s_dyn + logit_off);
+    int32_t *s_rank = reinterpret_cast<int32_t *>(s_dyn + logit_off + (size_t)MT * E * 8);
     int pre_expert = -1, pre_cnt = 0;
     if constexpr (PRE) {
         const int item = blockIdx.x / (I / 32);
@@ -328,39 +332,63 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 atomicOr(&s_mask[lane >> 6], 1ull << (lane & 63));
             }
         } else {
+            // more than 64 experts: the logits go to LDS and all waves rank them (below)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = lane + 64 * i;
+                if (e < E) { s_logit[t * E + e] = l[i]; s_rank[t * E + e] = 0; }
+            }
+        }
+    }
+    if (!PRE && E > 64) {
+        // Ranks in the order (larger first, lower index first among equals), counted by all eight
+        // waves, each over its share of the experts; the order is strict, so rank < k selects.  (k
+        // rounds of arg-max in the one wave of a token took 5.4 us for 128 experts and k = 8.)
+        __syncthreads();
+        if (s_flag != 0) {
+            for (int t = 0; t < T; ++t) {
+                if (E <= 128) wave::count_ranks<2, 4>(s_logit + t * E, s_rank + t * E, E, lane, wave, kWaves);
+                else wave::count_ranks<4, 2>(s_logit + t * E, s_rank + t * E, E, lane, wave, kWaves);
+            }
+        }
+        __syncthreads();
+        for (int t = wave; t < T && s_flag != 0; t += kWaves) {
+            double mine[4];
+            int rank[4];
             double mx = -INFINITY;
-    #pragma unroll
-            for (int i = 0; i < 4; ++i) mx = fmax(mx, l[i]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = lane + 64 * i;
+                const bool have = 64 * i < E && e < E;
+                mine[i] = have ? s_logit[t * E + e] : -INFINITY;
+                rank[i] = have ? s_rank[t * E + e] : MOE_MAX_EXPERTS;
+                mx = fmax(mx, mine[i]);
+            }
             mx = wave::max(mx);
             // the selection compares the fp64 logits; the softmax values only have to be good to
             // fp32, so they are computed in fp32 from the fp64 differences
-            float den = 0.f;
-    #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (lane + 64 * i < E) den += expf((float)(l[i] - mx));
-            den = wave::sum(den);
-            unsigned taken = 0;
-            float sel_sum = 0.f, my_conf = 0.f;
-            int my_id = 0;
-            for (int j = 0; j < k; ++j) {
-                double bv = -INFINITY;
-                int bi = wave::kNone;
-    #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int e = lane + 64 * i;
-                    if (e < E && !((taken >> i) & 1) && (bi == wave::kNone || l[i] > bv)) { bv = l[i]; bi = e; }
-                }
-                { const wave::Best b = wave::argmax(wave::Best{bv, bi}); bv = b.v; bi = b.i; }
-                if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-                const float p = expf((float)(bv - mx)) / den;
-                sel_sum += p;
-                if (lane == j) { my_conf = p; my_id = bi; }
+            float pe[4], den = 0.f, sel = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                pe[i] = rank[i] < MOE_MAX_EXPERTS ? expf((float)(mine[i] - mx)) : 0.f;
+                den += pe[i];
             }
-            if (lane < k) {
-                s_ids[t * k + lane] = my_id;
-                s_conf[t * k + lane] = my_conf;
-                s_w[t * k + lane] = a.renorm ? my_conf / sel_sum : my_conf;
-                atomicOr(&s_mask[my_id >> 6], 1ull << (my_id & 63));
+            den = wave::sum(den);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                pe[i] = pe[i] / den;
+                sel += rank[i] < k ? pe[i] : 0.f;
+            }
+            sel = wave::sum(sel);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (rank[i] < k) {
+                    const int e = lane + 64 * i;
+                    s_ids[t * k + rank[i]] = e;
+                    s_conf[t * k + rank[i]] = pe[i];
+                    s_w[t * k + rank[i]] = a.renorm ? pe[i] / sel : pe[i];
+                    atomicOr(&s_mask[e >> 6], 1ull << (e & 63));
+                }
             }
         }
     }
@@ -865,9 +893,10 @@ void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st
 
 // dynamic LDS: the bf16 copy of x (padded rows) and its per-group sums; with 8 tokens the
 // partial gate/up sums (8 waves x 4 row blocks x 4 x 32 floats) later take the same place
-size_t draft_dynamic_lds(int MT, int H, int g)
+size_t draft_dynamic_lds(int MT, int H, int g, int E)
 {
     size_t lds = (size_t)MT * (H + 8) * 2 + (size_t)MT * (H / g) * 4;
+    if (E > 64) lds = ((lds + 7) & ~(size_t)7) + (size_t)MT * E * 12;      // routing scratch: fp64 logits and ranks
     if (MT >= 8 && lds < (size_t)kWaves * 4 * 4 * 32 * 4) lds = (size_t)kWaves * 4 * 4 * 32 * 4;
     return lds;
 }
@@ -877,7 +906,7 @@ void launch_fused_t(const uint16_t *x, const FusedArgs &a, hipStream_t st, int m
 {
     const int maxu = PRE ? max_items : (a.E < a.T * a.k ? a.E : a.T * a.k);
     const dim3 grid(maxu * (a.I / 32)), block(kThreads);
-    const size_t lds = draft_dynamic_lds(MT, a.H, a.g);
+    const size_t lds = draft_dynamic_lds(MT, a.H, a.g, a.E);
     if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM, PRE>, grid, block, lds, st, x, a);
     else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM, PRE>, grid, block, lds, st, x, a);
     else launch_with_lds(draft_fused_kernel<MT, 4, SYM, PRE>, grid, block, lds, st, x, a);
@@ -927,7 +956,7 @@ bool draft_fits(const Shape &s, int tokens)
 {
     const int MT = tokens <= 1 ? 1 : (tokens <= 2 ? 2 : (tokens <= 4 ? 4 : 8));
     // 160 KiB of LDS per workgroup, 20 KiB of them for the kernel's static arrays
-    return draft_dynamic_lds(MT, s.H, s.g) <= (size_t)(160 - 20) * 1024;
+    return draft_dynamic_lds(MT, s.H, s.g, s.E) <= (size_t)(160 - 20) * 1024;
 }
 
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st)

@@ -96,8 +96,9 @@ __device__ inline Best argmax(Best b) { return all(b, [](Best x, Best y) { retur
 // first + stride, ... that come before logit e in the order (larger first, lower index first
 // among equals); with every e2 covered by some wave, rank[] becomes the position of each logit in
 // that strict order.  Lane l keeps logits l, l + 64, ... (NR of them, NR >= ceil(E / 64)) in
-// registers; the logits e2 are broadcast reads, eight in flight, compared without branches.
-template <int NR>
+// registers; the logits e2 are broadcast reads, kBatch in flight, compared without branches
+// (every comparison leaves a mask in scalar registers: a smaller batch where those are scarce).
+template <int NR, int kBatch = 8>
 __device__ inline void count_ranks(const double *logit, int32_t *rank, int E, int lane, int first, int stride)
 {
     double mine[NR];
@@ -108,15 +109,15 @@ __device__ inline void count_ranks(const double *logit, int32_t *rank, int E, in
         mine[i] = logit[e < E ? e : E - 1];
         part[i] = 0;
     }
-    for (int e2 = first; e2 < E; e2 += 8 * stride) {
-        double v[8];
+    for (int e2 = first; e2 < E; e2 += kBatch * stride) {
+        double v[kBatch];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < kBatch; ++j) {
             const int idx = e2 + j * stride;
             v[j] = logit[idx < E ? idx : E - 1];
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < kBatch; ++j) {
             const int idx = e2 + j * stride;
             const int live = idx < E ? 1 : 0;
 #pragma unroll
