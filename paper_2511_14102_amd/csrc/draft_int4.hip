@@ -58,6 +58,10 @@ constexpr uint32_t kSpinLimit = 1u << 22;
 // that the polls of hundreds of workgroups do not all land on one address.
 constexpr int kReplicas = kDraftSlotReplicas;
 constexpr int kTicketGroups = 16;
+// Up to this many experts the wave that polled a token's logits also selects its top-k by itself;
+// beyond, all waves share the ranking (two more barriers, which cost more than they save on few
+// experts: measured 1 us on 16 experts).
+constexpr int kLoneWaveTopk = 32;
 constexpr uint32_t kMagic = 0x43004300u;      // bf16 pair (128, 128)
 
 __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -203,7 +207,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     float *s_xsum = reinterpret_cast<float *>(s_dyn + (size_t)MT * xstride * 2);   // [MT][G]
     static_assert(!kRedOverX || sizeof(red_t) * kWaves == (size_t)kWaves * 4 * 4 * 32 * 4, "launcher sizes the dynamic LDS for this");
     red_t *s_red = reinterpret_cast<red_t *>(kRedOverX ? reinterpret_cast<float *>(s_dyn) : s_red_own);
-    // routing scratch behind the group sums, used with more than 64 experts: logits [MT][E] (fp64), ranks
+    // routing scratch behind the group sums, used with many experts: logits [MT][E] (fp64), ranks
     const size_t logit_off = ((size_t)MT * xstride * 2 + (size_t)MT * G * 4 + 7) & ~(size_t)7;
     double *s_logit = reinterpret_cast<double *>(s_dyn + logit_off);
     int32_t *s_rank = reinterpret_cast<int32_t *>(s_dyn + logit_off + (size_t)MT * E * 8);
@@ -306,7 +310,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
             if (!all) { if (lane == 0) s_flag = 0; continue; }
         }
-        if (E <= 64) {
+        if (E <= kLoneWaveTopk) {
             // Lane e holds logit e.  Its rank under (larger first, lower index first among equals) is
             // counted against every logit, read from its lane with a wave-uniform index: no
             // dependent chain of reductions per selected expert, and the order is strict, so the
@@ -332,7 +336,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 atomicOr(&s_mask[lane >> 6], 1ull << (lane & 63));
             }
         } else {
-            // more than 64 experts: the logits go to LDS and all waves rank them (below)
+            // many experts: the logits go to LDS and all waves rank them (below)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int e = lane + 64 * i;
@@ -340,14 +344,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
         }
     }
-    if (!PRE && E > 64) {
+    if (!PRE && E > kLoneWaveTopk) {
         // Ranks in the order (larger first, lower index first among equals), counted by all eight
         // waves, each over its share of the experts; the order is strict, so rank < k selects.  (k
         // rounds of arg-max in the one wave of a token took 5.4 us for 128 experts and k = 8.)
         __syncthreads();
         if (s_flag != 0) {
             for (int t = 0; t < T; ++t) {
-                if (E <= 128) wave::count_ranks<2, 4>(s_logit + t * E, s_rank + t * E, E, lane, wave, kWaves);
+                if (E <= 64) wave::count_ranks<1, 4>(s_logit + t * E, s_rank + t * E, E, lane, wave, kWaves);
+                else if (E <= 128) wave::count_ranks<2, 4>(s_logit + t * E, s_rank + t * E, E, lane, wave, kWaves);
                 else wave::count_ranks<4, 2>(s_logit + t * E, s_rank + t * E, E, lane, wave, kWaves);
             }
         }
@@ -896,7 +901,7 @@ void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st
 size_t draft_dynamic_lds(int MT, int H, int g, int E)
 {
     size_t lds = (size_t)MT * (H + 8) * 2 + (size_t)MT * (H / g) * 4;
-    if (E > 64) lds = ((lds + 7) & ~(size_t)7) + (size_t)MT * E * 12;      // routing scratch: fp64 logits and ranks
+    if (E > kLoneWaveTopk) lds = ((lds + 7) & ~(size_t)7) + (size_t)MT * E * 12;   // routing scratch: fp64 logits and ranks
     if (MT >= 8 && lds < (size_t)kWaves * 4 * 4 * 32 * 4) lds = (size_t)kWaves * 4 * 4 * 32 * 4;
     return lds;
 }

@@ -52,19 +52,6 @@ __device__ inline double from_lane(double v, int lane) {
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
-// Largest value over the wave with its index; among equal values the lower index wins.  A lane
-// with nothing to offer passes index kNone.  (value, index) pairs are ordered strictly, so both
-// partners of a step keep the same pair.
-constexpr int kNone = 0x7fffffff;
-struct Best { double v; int i; };
-__device__ inline Best better(Best a, Best b) {
-    const bool take = b.i != kNone && (a.i == kNone || b.v > a.v || (b.v == a.v && b.i < a.i));
-    return take ? b : a;
-}
-template <int kCtrl>
-__device__ inline Best move(Best b) { return Best{move<kCtrl>(b.v), move<kCtrl>(b.i)}; }
-template <int kLane>
-__device__ inline Best from_lane(Best b) { return Best{from_lane<kLane>(b.v), from_lane<kLane>(b.i)}; }
 // Reduction over each row of 16 lanes with a commutative `op`; every lane of the row gets the
 // row's result.  After the two quad steps a quad's lanes agree, so the mirror moves pair
 // disjoint, already reduced groups.
@@ -89,7 +76,6 @@ __device__ inline double sum(double v) { return all(v, [](double a, double b) { 
 __device__ inline double max(double v) { return all(v, [](double a, double b) { return fmax(a, b); }); }
 __device__ inline float row_sum(float v) { return row_all(v, [](float a, float b) { return a + b; }); }
 
-__device__ inline Best argmax(Best b) { return all(b, [](Best x, Best y) { return better(x, y); }); }
 
 // Rank counting for a top-k selection by several waves.  logit[0 .. E) and rank[0 .. E) live in
 // LDS, rank zeroed.  The calling wave adds to rank[e] the number of logits e2 = first,
