@@ -28,8 +28,9 @@
  * Limits: 1 <= T <= MOE_MAX_TOKENS (draft: MOE_MAX_DRAFT_TOKENS), E <= MOE_MAX_EXPERTS,
  * k <= min(E, MOE_MAX_TOPK), T * k <= MOE_MAX_ASSIGN, S <= MOE_MAX_SHARED, H and I multiples
  * of 64, g in {32, 64, 128} dividing both H and I.  A draft call keeps a copy of its tokens in
- * LDS: T * (2 H + 16 + 4 H / g) bytes, T rounded up to 1, 2, 4 or 8, must stay under 140 KiB
- * (H <= 8192 for 8 tokens and for the prefill call, <= 16384 for 4), else MOE_ERR_INVALID_ARG.
+ * LDS: T * (2 H + 16 + 4 H / g) bytes, plus 12 T E bytes of routing scratch when E > 32, T rounded
+ * up to 1, 2, 4 or 8, must stay under 140 KiB (H <= 8192 for 8 tokens and for the prefill call,
+ * <= 16384 for 4), else MOE_ERR_INVALID_ARG (moe_draft_call_fits tells).
  *
  * Kernel-native weight layouts (part of the ABI; pack.py builds them from row-major arrays)
  *
@@ -136,6 +137,10 @@ const char *moe_last_hip_error(const moe_ctx *ctx);
 /* MOE_OK if `desc` is a shape the kernels support (the limits above), else
  * MOE_ERR_INVALID_ARG.  Needs no device. */
 int moe_validate_desc(const moe_layer_desc *desc);
+
+/* MOE_OK if a draft call with T tokens (1 .. MOE_MAX_DRAFT_TOKENS; the prefill call counts as 8)
+ * fits the LDS limit stated above for this shape, else MOE_ERR_INVALID_ARG.  Needs no device. */
+int moe_draft_call_fits(const moe_layer_desc *desc, int T);
 
 /* Sizes of the packed weight blobs of one expert (0 if desc is invalid). */
 size_t moe_bf16_expert_bytes(const moe_layer_desc *desc);

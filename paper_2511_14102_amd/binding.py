@@ -18,6 +18,7 @@ MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_MISSING_EXP
 
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_status_string", "moe_last_hip_error", "moe_validate_desc",
+    "moe_draft_call_fits",
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
     "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
     "moe_draft_layer_int4", "moe_prefill_workspace_bytes", "moe_draft_prefill_int4", "moe_expert_union",
@@ -77,6 +78,7 @@ def load_library():
         L.moe_status_string.argtypes = [i32]; L.moe_status_string.restype = ctypes.c_char_p
         L.moe_last_hip_error.argtypes = [vp]; L.moe_last_hip_error.restype = ctypes.c_char_p
         L.moe_validate_desc.argtypes = [dp]
+        L.moe_draft_call_fits.argtypes = [dp, i32]
         for n in ("moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
                   "moe_int4_expert_scale_bytes"):
             getattr(L, n).argtypes = [dp]; getattr(L, n).restype = sz
@@ -112,6 +114,10 @@ def status_string(status: int) -> str:
 
 def validate_desc(desc: LayerDesc) -> int:
     return load_library().moe_validate_desc(ctypes.byref(desc))
+
+
+def draft_call_fits(desc: LayerDesc, T: int) -> int:
+    return load_library().moe_draft_call_fits(ctypes.byref(desc), T)
 
 
 def bf16_expert_bytes(desc: LayerDesc) -> int:

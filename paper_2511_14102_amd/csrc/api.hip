@@ -206,6 +206,12 @@ const char *moe_last_hip_error(const moe_ctx *ctx) { return ctx ? ctx->hip_error
 
 int moe_validate_desc(const moe_layer_desc *desc) { return check_desc(desc); }
 
+int moe_draft_call_fits(const moe_layer_desc *desc, int T)
+{
+    if (check_desc(desc) != MOE_OK || check_tokens(desc, T, MOE_MAX_DRAFT_TOKENS) != MOE_OK) return MOE_ERR_INVALID_ARG;
+    return draft_fits(make_shape(desc, T), T) ? MOE_OK : MOE_ERR_INVALID_ARG;
+}
+
 size_t moe_bf16_expert_bytes(const moe_layer_desc *d)
 {
     if (check_desc(d) != MOE_OK) return 0;

@@ -180,6 +180,18 @@ def test_host_only_entry_points():
     with pytest.raises(B.MoeError):
         B.workspace_bytes(d, 17)
     assert B.status_string(0) == "ok" and "resident" in B.status_string(-4)
+    # the token copy of a draft call must fit into LDS: T (2 H + 16 + 4 H / g) <= 140 KiB, T rounded
+    # up to 1, 2, 4, 8 (the formula of the header, evaluated here)
+    for H, g in ((4096, 128), (8192, 32), (8192, 128), (12288, 128), (16384, 128), (32768, 128), (65536, 128)):
+        dd = B.LayerDesc(H, 4, 128, 1, 0, g, 1)
+        assert B.validate_desc(dd) == 0
+        for T in range(1, 9):
+            cap = 1 if T <= 1 else 2 if T <= 2 else 4 if T <= 4 else 8
+            fits = cap * (2 * H + 16 + 4 * H // g) <= 140 * 1024
+            assert (B.draft_call_fits(dd, T) == 0) == fits, (H, g, T)
+    assert B.draft_call_fits(B.LayerDesc(4096, 4, 128, 1, 0, 128, 1), 9) == B.MOE_ERR_INVALID_ARG
+    many = B.LayerDesc(8192, 256, 128, 8, 0, 128, 1)          # 8 (2 H + 16 + 4 H / g) + 12 * 8 * 256 > 140 KiB
+    assert B.draft_call_fits(many, 8) == B.MOE_ERR_INVALID_ARG and B.draft_call_fits(many, 4) == 0
     # prefill: any number of tokens up to the limit
     d = B.LayerDesc.from_config(base)
     assert B.prefill_workspace_bytes(d, 1) > 0
