@@ -27,10 +27,13 @@
  * size, S shared experts.  Assignment index a = t * k + j (token-major, j = rank).
  * Limits: 1 <= T <= MOE_MAX_TOKENS (draft: MOE_MAX_DRAFT_TOKENS), E <= MOE_MAX_EXPERTS,
  * k <= min(E, MOE_MAX_TOPK), T * k <= MOE_MAX_ASSIGN, S <= MOE_MAX_SHARED, H and I multiples
- * of 64, g in {32, 64, 128} dividing both H and I.  A draft call keeps a copy of its tokens in
- * LDS: T * (2 H + 16 + 4 H / g) bytes, plus 12 T E bytes of routing scratch when E > 32, T rounded
- * up to 1, 2, 4 or 8, must stay under 140 KiB (H <= 8192 for 8 tokens and for the prefill call,
- * <= 16384 for 4), else MOE_ERR_INVALID_ARG (moe_draft_call_fits tells).
+ * of 64, g in {32, 64, 128} dividing both H and I.  What a draft call keeps in LDS must stay under
+ * 140 KiB, else MOE_ERR_INVALID_ARG (moe_draft_call_fits tells).  One token: 2 H + 16 + 4 H / g bytes
+ * (its copy and group sums), plus 12 E + 8 bytes of routing scratch when E > 32 (H <= 65536).  Two to
+ * eight tokens, T rounded up to 2, 4 or 8: T (2 H + 16 + 4 H / g) + 12 T E bytes (rounded up to 16) plus
+ * 16 KiB x (ceil(ceil(H / g / 8) / 4) + ceil(ceil(H / 64 / 8) / 4)) for the scale / zero entries of one
+ * work item (in the symmetric format H / g and H / 64 count pairs).  The prefill call needs
+ * 8 (2 H + 16 + 4 H / g) bytes.
  *
  * Kernel-native weight layouts (part of the ABI; pack.py builds them from row-major arrays)
  *

@@ -209,7 +209,7 @@ int moe_validate_desc(const moe_layer_desc *desc) { return check_desc(desc); }
 int moe_draft_call_fits(const moe_layer_desc *desc, int T)
 {
     if (check_desc(desc) != MOE_OK || check_tokens(desc, T, MOE_MAX_DRAFT_TOKENS) != MOE_OK) return MOE_ERR_INVALID_ARG;
-    return draft_fits(make_shape(desc, T), T) ? MOE_OK : MOE_ERR_INVALID_ARG;
+    return draft_fits(make_shape(desc, T), T, false) ? MOE_OK : MOE_ERR_INVALID_ARG;
 }
 
 size_t moe_bf16_expert_bytes(const moe_layer_desc *d)
@@ -274,11 +274,10 @@ int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
     return hip_status(ctx, hipGetLastError());
 }
 
-int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
-                         const void *x, const void *wr, const float *bias,
-                         const moe_int4_experts *routed, const void *shared, int T,
-                         float *y, int32_t *ids_out, float *conf_out,
-                         void *workspace, size_t workspace_bytes, void *stream)
+// Argument checks of a draft call (everything but the workspace)
+static int check_draft_args(moe_ctx *ctx, const moe_layer_desc *desc, const void *x, const void *wr,
+                            const float *bias, const moe_int4_experts *routed, const void *shared, int T,
+                            const float *y, const int32_t *ids_out, const float *conf_out)
 {
     if (!ctx || check_desc(desc) != MOE_OK || check_tokens(desc, T, MOE_MAX_DRAFT_TOKENS) != MOE_OK)
         return MOE_ERR_INVALID_ARG;
@@ -293,13 +292,18 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         routed->expert_stride_sz < sz_bytes)
         return MOE_ERR_INVALID_ARG;
     if (desc->n_shared > 0 && !shared) return MOE_ERR_INVALID_ARG;
-    const Shape s = make_shape(desc, T);
-    if (!draft_fits(s, T)) return MOE_ERR_INVALID_ARG;     // hidden size too large for T tokens per call
-    const WsLayout L = ws_layout(*desc, T);
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    if (!draft_fits(make_shape(desc, T), T, routed->symmetric != 0)) return MOE_ERR_INVALID_ARG;     // hidden size too large for T tokens per call
+    return MOE_OK;
+}
 
-    hipStream_t st = (hipStream_t)stream;
-    char *ws = (char *)workspace;
+// The launches of a draft call on checked arguments; ws: the call's scratch, laid out by L.
+// timed: launches may carry profiling event pairs (which allocates on first use).
+static int enqueue_draft(moe_ctx *ctx, const moe_layer_desc *desc, const void *x, const void *wr,
+                         const float *bias, const moe_int4_experts *routed, const void *shared, int T,
+                         float *y, int32_t *ids_out, float *conf_out, char *ws, const WsLayout &L,
+                         hipStream_t st, bool timed)
+{
+    const Shape s = make_shape(desc, T);
     Plan *plan = (Plan *)(ws + L.plan);
     DraftFusedArgs a;
     memset(&a, 0, sizeof a);
@@ -312,7 +316,16 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     a.tickets = (uint32_t *)(ws + L.tickets);
     a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
     a.plan = plan; a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
-    { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_fused(s, a, st); }
+    if (!timed) {
+        launch_draft_fused(s, a, ctx->n_cu, st);
+        if (s.S > 0) {
+            launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, ws + L.hb_lo, st);
+            launch_bf16_down(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, (float *)(ws + L.obuf), st);
+            launch_combine(s, plan, nullptr, 0, (const float *)(ws + L.obuf), 1, 0, y, st);
+        }
+        return hip_status(ctx, hipGetLastError());
+    }
+    { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_fused(s, a, ctx->n_cu, st); }
     if (s.S > 0) {   // shared experts stay 16-bit in the draft model (section 3.4.2)
         { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st);
           launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, ws + L.hb_lo, st); }
@@ -322,6 +335,20 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
           launch_combine(s, plan, nullptr, 0, (const float *)(ws + L.obuf), 1, 0, y, st); }
     }
     return hip_status(ctx, hipGetLastError());
+}
+
+int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
+                         const void *x, const void *wr, const float *bias,
+                         const moe_int4_experts *routed, const void *shared, int T,
+                         float *y, int32_t *ids_out, float *conf_out,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int rc = check_draft_args(ctx, desc, x, wr, bias, routed, shared, T, y, ids_out, conf_out);
+    if (rc != MOE_OK) return rc;
+    const WsLayout L = ws_layout(*desc, T);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
+    return enqueue_draft(ctx, desc, x, wr, bias, routed, shared, T, y, ids_out, conf_out, (char *)workspace, L,
+                         (hipStream_t)stream, true);
 }
 
 // workspace of a prefill call: routing weights and sorted assignment indices [T k], the item
@@ -384,7 +411,7 @@ int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         routed->expert_stride_sz < sz_bytes)
         return MOE_ERR_INVALID_ARG;
     const Shape s = make_shape(desc, T);
-    if (!draft_fits(s, kPrefillChunk)) return MOE_ERR_INVALID_ARG;
+    if (!draft_prefill_fits(s)) return MOE_ERR_INVALID_ARG;
     const PrefillLayout L = prefill_layout(*desc, T);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
 

@@ -105,7 +105,7 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
 constexpr int kPrefillChunk = 8;
 struct PrefillItem { int32_t expert, first, cnt, pad; };
 
-// draft_int4.hip
+// draft_int4.hip (a call of 2 to 8 tokens) and draft_slice.hip (one token; a routed run of tokens)
 struct DraftFusedArgs {
     const void *x, *wr; const float *bias;
     const void *q, *sz; size_t stride_q, stride_sz;
@@ -115,11 +115,17 @@ struct DraftFusedArgs {
     Plan *plan; const void *shared; size_t shared_stride;
     const PrefillItem *items; const int32_t *n_items; const int32_t *sorted; const float *w_all;   // prerouted only
 };
-void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
-// whether the x copy of a call with `tokens` tokens per workgroup (1-8) fits into LDS
-bool draft_fits(const Shape &s, int tokens);
+// n_cu: compute units of the device (the launch is persistent, at most one workgroup per unit)
+void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, int n_cu, hipStream_t st);
+// whether the x copy and the entry buffers of a call with `tokens` tokens (1-8) fit into LDS
+bool draft_fits(const Shape &s, int tokens, bool symmetric);
+// draft_slice.hip: one workgroup per (expert, slice) work item
 // grid sized for max_items work items; y must have been cleared
 void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &a, int max_items, hipStream_t st);
+bool draft_prefill_fits(const Shape &s);
+// the call with ONE token (router inside the launch)
+void launch_draft_one_token(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
+bool draft_one_token_fits(const Shape &s);
 void launch_zero(void *p, size_t bytes, hipStream_t st);
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st);
 

@@ -1,8 +1,12 @@
-"""The draft kernel must not spill vector registers: its in-flight windows are sized to the 128
-registers a wave has with two workgroups per compute unit, and a spilled window turns the
-weight stream into scratch-memory traffic (measured: 36.8 us instead of 29.6 us per call on the
-phi shape with 12 spilled registers).  The check compiles the kernel file for gfx950 and reads
-the spill counts from the assembly's kernel descriptors; it needs hipcc but no GPU."""
+"""Build-time checks of the draft kernels' machine code (hipcc only, no GPU).
+
+No instantiation may spill vector registers: the in-flight tile windows live in registers, and
+a spilled window turns the weight stream into scratch-memory traffic (measured once: 36.8 us
+instead of 29.6 us per call on the phi shape with 12 spilled registers).
+
+The streaming kernel copies scale / zero entries into LDS with loads issued from inline assembly
+that set the M0 register themselves; the compiler is not told, so nothing else in those kernels
+may depend on M0."""
 import os
 import re
 import subprocess
@@ -11,26 +15,42 @@ import tempfile
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_draft_kernel_instantiations_do_not_spill():
+def _assembly(name):
     from paper_2511_14102_amd import build as B
-    src = os.path.join(B.CSRC, "draft_int4.hip")
+    src = os.path.join(B.CSRC, name)
     with tempfile.TemporaryDirectory() as tmp:
-        out = os.path.join(tmp, "draft_int4.s")
+        out = os.path.join(tmp, name + ".s")
         cmd = [B.HIPCC] + B.FLAGS + ["--cuda-device-only", "-S", src, "-o", out]
         r = subprocess.run(cmd, capture_output=True, text=True)
         assert r.returncode == 0, r.stderr[-2000:]
-        text = open(out).read()
-    names = re.findall(r"\.name:\s+(\S*draft_fused_kernel\S*)", text)
-    spills = re.findall(r"\.vgpr_spill_count:\s+(\d+)", text)
-    sgpr_spills = re.findall(r"\.sgpr_spill_count:\s+(\d+)", text)
-    assert len(names) >= 24                          # 4 token capacities x 3 group sizes x 2 formats
-    blocks = text.split(".name:")
+        return open(out).read()
+
+
+def _kernel_blocks(text, kernel):
+    """Metadata blocks (one per kernel, after '.name:') of the instantiations of `kernel`."""
+    return [blk for blk in text.split(".name:")[1:] if kernel in blk.split("\n", 1)[0]]
+
+
+def test_draft_kernel_instantiations_do_not_spill():
     checked = 0
-    for blk in blocks[1:]:
-        if "draft_fused_kernel" not in blk.split("\n", 1)[0]:
-            continue
-        m = re.search(r"\.vgpr_spill_count:\s+(\d+)", blk)
-        assert m is not None
-        assert int(m.group(1)) == 0, blk.split("\n", 1)[0].strip()
-        checked += 1
-    assert checked >= 24
+    for src, kernel, expect in (("draft_int4.hip", "draft_stream_kernel", 18),     # 3 token capacities x 3 group sizes x 2 formats
+                                ("draft_slice.hip", "draft_fused_kernel", 12)):    # (one token, prefill) x 3 group sizes x 2 formats
+        text = _assembly(src)
+        blocks = _kernel_blocks(text, kernel)
+        assert len(blocks) >= expect, (src, len(blocks))
+        for blk in blocks:
+            m = re.search(r"\.vgpr_spill_count:\s+(\d+)", blk)
+            assert m is not None
+            assert int(m.group(1)) == 0, blk.split("\n", 1)[0].strip()
+            checked += 1
+    assert checked >= 30
+
+
+def test_streaming_kernel_uses_m0_only_for_its_loads_to_lds():
+    text = _assembly("draft_int4.hip")
+    body = text.split("draft_stream_kernel", 1)[1]
+    uses = [l.strip() for l in body.splitlines() if re.search(r"\bm0\b", l) and not l.strip().startswith(";")]
+    assert uses, "the loads to LDS are gone?"
+    for l in uses:
+        assert l.startswith("s_mov_b32 m0,"), l
+    assert "global_load_lds_dwordx4" in body

@@ -180,18 +180,35 @@ def test_host_only_entry_points():
     with pytest.raises(B.MoeError):
         B.workspace_bytes(d, 17)
     assert B.status_string(0) == "ok" and "resident" in B.status_string(-4)
-    # the token copy of a draft call must fit into LDS: T (2 H + 16 + 4 H / g) <= 140 KiB, T rounded
-    # up to 1, 2, 4, 8 (the formula of the header, evaluated here)
+    # what a draft call keeps in LDS must fit in 140 KiB (the formula of the header, evaluated here).  One
+    # token: its copy 2 H + 16 + 4 H / g, plus 12 E of routing scratch when E > 32.  More tokens (T rounded
+    # up to 2, 4, 8): the copy T (2 H + 16 + 4 H / g), 12 T E of routing scratch, and per wave (8) two copies
+    # of the scale / zero entries of its share of one work item in whole KiB.
+    def lds_need(H, g, E, cap, sym=False):
+        if cap == 1:
+            return 2 * H + 16 + 4 * H // g + (12 * E + 8 if E > 32 else 0)
+        need = (cap * (2 * H + 16 + 4 * H // g) + 7) // 8 * 8 + 12 * cap * E
+        need = (need + 15) // 16 * 16
+        epl = 2 if sym else 1
+        nw = 8                                             # waves of the workgroup
+        blocks = lambda n: ((n // epl + nw - 1) // nw + 3) // 4
+        return need + 2 * nw * (blocks(H // g) + blocks(H // 64)) * 1024
     for H, g in ((4096, 128), (8192, 32), (8192, 128), (12288, 128), (16384, 128), (32768, 128), (65536, 128)):
         dd = B.LayerDesc(H, 4, 128, 1, 0, g, 1)
         assert B.validate_desc(dd) == 0
         for T in range(1, 9):
             cap = 1 if T <= 1 else 2 if T <= 2 else 4 if T <= 4 else 8
-            fits = cap * (2 * H + 16 + 4 * H // g) <= 140 * 1024
+            fits = lds_need(H, g, 4, cap) <= 140 * 1024
             assert (B.draft_call_fits(dd, T) == 0) == fits, (H, g, T)
     assert B.draft_call_fits(B.LayerDesc(4096, 4, 128, 1, 0, 128, 1), 9) == B.MOE_ERR_INVALID_ARG
-    many = B.LayerDesc(8192, 256, 128, 8, 0, 128, 1)          # 8 (2 H + 16 + 4 H / g) + 12 * 8 * 256 > 140 KiB
-    assert B.draft_call_fits(many, 8) == B.MOE_ERR_INVALID_ARG and B.draft_call_fits(many, 4) == 0
+    seen = set()
+    for H in (4096, 6144, 8192):                       # many experts: the routing scratch counts
+        many = B.LayerDesc(H, 256, 128, 8, 0, 128, 1)
+        for T in (1, 2, 4, 8):
+            fits = lds_need(H, 128, 256, T) <= 140 * 1024
+            assert (B.draft_call_fits(many, T) == 0) == fits, (H, T)
+            seen.add(fits)
+    assert seen == {True, False}
     # prefill: any number of tokens up to the limit
     d = B.LayerDesc.from_config(base)
     assert B.prefill_workspace_bytes(d, 1) > 0
