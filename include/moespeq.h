@@ -224,6 +224,28 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * moe_draft_layer_int4 for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * mathematics and outputs as moe_draft_layer_int4 minus the workspace: the scratch is a static
+ * device array inside the library, moe_noalloc_scratch_bytes() = 2 MiB per GPU, held until the
+ * process ends.  The call allocates nothing (no hipMalloc / hipFree, no event creation: launches
+ * of this call are never given profiling event pairs) and enqueues a fill kernel that clears the
+ * part of the array the draft kernel needs zero, then the launches of moe_draft_layer_int4.
+ * Shapes whose workspace (moe_workspace_bytes(desc, T)) exceeds the array return
+ * MOE_ERR_WORKSPACE with nothing enqueued; the context's device must be the current device
+ * (else MOE_ERR_INVALID_ARG).  All calls on one GPU share the one array: calls that overlap on a
+ * GPU (two streams, two contexts) race; order them on one stream or with events.
+ */
+size_t moe_noalloc_scratch_bytes(void);
+int moe_draft_layer_int4_noalloc(moe_ctx *ctx, const moe_layer_desc *desc,
+                                 const void *x_bf16, const void *w_router_bf16,
+                                 const float *router_bias,
+                                 const moe_int4_experts *routed, const void *shared_bf16,
+                                 int T,
+                                 float *y_f32, int32_t *ids_out, float *conf_out,
+                                 void *stream);
+
+/*
  * The draft model over a long run of tokens (the prompt).  Section 3.4.2-3.4.3 describe the
  * int4 layer and choose its backend for the prefill stage as well as the decode stage (the
  * figure comparing backends there).  Same mathematics, arguments and outputs as moe_draft_layer_int4 for 1 <= T <=

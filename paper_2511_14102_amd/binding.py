@@ -21,7 +21,8 @@ EXPORTS = [
     "moe_draft_call_fits",
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
     "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
-    "moe_draft_layer_int4", "moe_prefill_workspace_bytes", "moe_draft_prefill_int4", "moe_expert_union",
+    "moe_draft_layer_int4", "moe_noalloc_scratch_bytes", "moe_draft_layer_int4_noalloc",
+    "moe_prefill_workspace_bytes", "moe_draft_prefill_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
     "moe_profile_enable", "moe_profile_read", "moe_kernel_name", "moe_stream_read_probe",
 ]
@@ -87,6 +88,9 @@ def load_library():
         L.moe_route_topk.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_draft_layer_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                            vp, vp, vp, vp, sz, vp]
+        L.moe_noalloc_scratch_bytes.argtypes = []; L.moe_noalloc_scratch_bytes.restype = sz
+        L.moe_draft_layer_int4_noalloc.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
+                                                   vp, vp, vp, vp]
         L.moe_prefill_workspace_bytes.argtypes = [dp, i32, ctypes.POINTER(sz)]
         L.moe_draft_prefill_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                              vp, vp, vp, vp, sz, vp]
@@ -102,7 +106,7 @@ def load_library():
         for n in EXPORTS:
             if n not in ("moe_status_string", "moe_last_hip_error", "moe_bf16_expert_bytes",
                          "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
-                         "moe_int4_expert_scale_bytes", "moe_kernel_name"):
+                         "moe_int4_expert_scale_bytes", "moe_kernel_name", "moe_noalloc_scratch_bytes"):
                 getattr(L, n).restype = i32
         _lib = L
     return _lib
@@ -142,6 +146,10 @@ def workspace_bytes(desc: LayerDesc, max_tokens: int) -> int:
     if rc != MOE_OK:
         raise MoeError(rc, "moe_workspace_bytes")
     return out.value
+
+
+def noalloc_scratch_bytes() -> int:
+    return load_library().moe_noalloc_scratch_bytes()
 
 
 def prefill_workspace_bytes(desc: LayerDesc, T: int) -> int:
@@ -212,6 +220,14 @@ class Context:
             self._h, ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), ctypes.byref(ex),
             _ptr(shared_bf16), T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream(stream)), "moe_draft_layer_int4")
+
+    def draft_layer_int4_noalloc(self, desc, x, w_router, router_bias, q_blob, sz_blob, stride_q, stride_sz,
+                                 shared_bf16, T, y_f32, ids_out, conf_out, stream=None, symmetric=False):
+        ex = Int4Experts(q_blob.data_ptr(), sz_blob.data_ptr(), stride_q, stride_sz, int(bool(symmetric)))
+        self._check(self._lib.moe_draft_layer_int4_noalloc(
+            self._h, ctypes.byref(desc), _ptr(x), _ptr(w_router), _ptr(router_bias), ctypes.byref(ex),
+            _ptr(shared_bf16), T, _ptr(y_f32), _ptr(ids_out), _ptr(conf_out), _stream(stream)),
+            "moe_draft_layer_int4_noalloc")
 
     def draft_prefill_int4(self, desc, x, w_router, router_bias, q_blob, sz_blob, stride_q, stride_sz,
                            shared_bf16, T, y_f32, ids_out, conf_out, workspace, stream=None, symmetric=False):

@@ -10,12 +10,20 @@
 struct moe_ctx {
     int device;
     int n_cu;
+    void *scratch;          // this device's address of the static scratch array
     char arch[64];
     char hip_error[128];
     bool profiling;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs[MOE_KERNEL_COUNT];   // recorded, not yet read
     std::vector<hipEvent_t> free_events;
 };
+
+// Scratch of the allocation-free draft call (moe_draft_layer_int4_noalloc).  Every GPU the library
+// runs on holds its own copy of the array, at its own address, until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call
+// returned (moe_create asks once per context, with the context's device current).
+constexpr size_t kStaticScratchBytes = (size_t)2 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace moespeq {
 
@@ -128,6 +136,18 @@ int moe_create(moe_ctx **out, int device)
     c->profiling = false;
     c->device = device;
     c->n_cu = prop.multiProcessorCount;
+    {
+        int prev = 0;
+        hipError_t e = hipGetDevice(&prev);
+        if (e == hipSuccess) e = hipSetDevice(device);
+        void *p = nullptr;
+        if (e == hipSuccess) {
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            (void)hipSetDevice(prev);
+        }
+        if (e != hipSuccess || !p) { delete c; return MOE_ERR_HIP; }
+        c->scratch = p;
+    }
     strncpy(c->arch, prop.gcnArchName, sizeof(c->arch) - 1);
     *out = c;
     return MOE_OK;
@@ -349,6 +369,28 @@ int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
     return enqueue_draft(ctx, desc, x, wr, bias, routed, shared, T, y, ids_out, conf_out, (char *)workspace, L,
                          (hipStream_t)stream, true);
+}
+
+size_t moe_noalloc_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int moe_draft_layer_int4_noalloc(moe_ctx *ctx, const moe_layer_desc *desc,
+                                 const void *x, const void *wr, const float *bias,
+                                 const moe_int4_experts *routed, const void *shared, int T,
+                                 float *y, int32_t *ids_out, float *conf_out, void *stream)
+{
+    const int rc = check_draft_args(ctx, desc, x, wr, bias, routed, shared, T, y, ids_out, conf_out);
+    if (rc != MOE_OK) return rc;
+    const WsLayout L = ws_layout(*desc, T);
+    if (L.total > kStaticScratchBytes) return MOE_ERR_WORKSPACE;     // shape beyond the static scratch array
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device) return MOE_ERR_INVALID_ARG;   // ctx->scratch is this device's copy
+    char *ws = (char *)ctx->scratch;         // the device address from hipGetSymbolAddress, never the array's name
+    hipStream_t st = (hipStream_t)stream;
+    // The array keeps whatever the last call on this GPU left.  The part that must start at zero
+    // (ticket counters and exchange slots) is cleared by a fill kernel, which is also safe
+    // under stream capture.
+    launch_zero(ws + L.tickets, L.plan - L.tickets, st);
+    return enqueue_draft(ctx, desc, x, wr, bias, routed, shared, T, y, ids_out, conf_out, ws, L, st, false);
 }
 
 // workspace of a prefill call: routing weights and sorted assignment indices [T k], the item
