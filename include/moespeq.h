@@ -111,7 +111,7 @@ typedef struct moe_layer_desc {
     int32_t inter;         /* I */
     int32_t top_k;         /* k */
     int32_t n_shared;      /* S always-on shared experts (bf16 in both passes) */
-    int32_t group_size;    /* g (draft only; ignored by route / verify) */
+    int32_t group_size;    /* g in {32, 64, 128} (used by the draft calls; every call validates it) */
     int32_t renormalize;   /* nonzero: routing weights divided by their sum over the k */
 } moe_layer_desc;
 
@@ -157,11 +157,41 @@ size_t moe_int4_expert_scale_bytes(const moe_layer_desc *desc);
 int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *bytes);
 
 /* Puts a workspace into its idle state (enqueues a fill kernel on `stream`; workspace_bytes a
- * multiple of 4).  Required once after allocation, before the first draft call: the draft
- * kernel exchanges the router result between its workgroups through tagged slots and a ticket
- * counter there, which it expects zero on entry and leaves zero on exit (also when the call
- * is replayed from a HIP graph).  Nothing else is carried from call to call. */
+ * multiple of 4).  Required once after allocation, before the first moe_draft_layer_int4 OR
+ * moe_verify_layer_bf16 call on it, and again after a draft call that timed out (below).  The first
+ * 256 bytes and the slot area behind them hold what the kernels exchange between their workgroups:
+ * the draft kernels' ticket counters and tagged router-result slots, the verify call's arrival
+ * counter, and the draft status word.  Both calls expect the counters and tags zero on entry and
+ * leave them zero on exit (also when the call is replayed from a HIP graph); nothing else is
+ * carried from call to call. */
 int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Size of the leading part of a workspace that holds the "idle state": 256 bytes of counters and
+ * the status word, all zero whenever no call is running, then 16-byte router-exchange slots
+ * {8 bytes of logit, 8 bytes of tag} whose tags are zero then.  It does not depend on the token
+ * count. */
+int moe_workspace_idle_bytes(const moe_layer_desc *desc, size_t *bytes);
+
+/* Outcome of the draft calls that used `workspace` since its last moe_workspace_init. */
+#define MOE_DRAFT_OK          0
+#define MOE_DRAFT_TIMED_OUT   1
+/*
+ * Inside a draft launch the workgroups that reduce the router rows hand the logits to all others,
+ * which poll for them a bounded number of times (moe_set_draft_spin_limit; default 2^22 polls,
+ * seconds).  The wait ends only if the producing workgroups run while the others poll.  The
+ * library checks on the host that the launch fits the device at once (else the call returns
+ * MOE_ERR_INVALID_ARG), which is enough on a device that runs nothing else; kernels of other
+ * streams or processes that hold compute units can delay the producers.  If a workgroup runs out of
+ * polls it skips its work: the call still returns MOE_OK (the launch was enqueued), ids_out holds
+ * -1 (conf_out 0), y is unspecified, the status word in the workspace is set and stays set, and the
+ * counters may be left non-zero.  moe_draft_status waits for `stream`, reads the word and writes
+ * MOE_DRAFT_OK or MOE_DRAFT_TIMED_OUT to *status (HOST pointer).  After a time-out call
+ * moe_workspace_init before the workspace is used again.  (moe_draft_layer_int4_noalloc clears its
+ * scratch on every call; its status is not kept.)
+ */
+int moe_set_draft_spin_limit(moe_ctx *ctx, uint32_t polls);          /* polls >= 1 */
+int moe_draft_status(moe_ctx *ctx, const void *workspace, size_t workspace_bytes,
+                     int32_t *status, void *stream);
 
 /* ---- router: softmax + top-k, histogram, permutation --------------------------------- */
 
@@ -213,7 +243,8 @@ int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
  * copied to the host at once (section 4.1.2, batched device-to-host transfer).
  * `workspace` must be in its idle state (moe_workspace_init once; every draft call restores
  * it).  y is summed with fp32 atomics, so its last bits may differ from run to run; ids and
- * confidences do not.
+ * confidences do not.  ids_out = -1 marks a call whose bounded wait ran out (moe_draft_status).
+ * Returns MOE_ERR_INVALID_ARG also when the launch would not fit the device at once.
  */
 int moe_draft_layer_int4(moe_ctx *ctx, const moe_layer_desc *desc,
                          const void *x_bf16, const void *w_router_bf16,
@@ -307,7 +338,9 @@ int moe_expert_union(moe_ctx *ctx, const int32_t *ids, int n_ids, int n_experts,
  * *n_missing != 0 (y is then still the partial sum).
  *
  * 1 <= T <= MOE_MAX_TOKENS.  y_bf16 [T,H]; ids_out [T,k] int32 or NULL; missing [E] int32 and
- * n_missing [1] int32 device memory, required.
+ * n_missing [1] int32 device memory, required.  `workspace` must have been put into its idle
+ * state once (moe_workspace_init): the launch that routes counts its arriving workgroups there
+ * and leaves the counter zero again.
  */
 int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
                           const void *x_bf16, const void *w_router_bf16,

@@ -14,13 +14,15 @@ _lib = None
 MOE_VERIFY_ACCUMULATE = 1
 MOE_VERIFY_ONLY_LISTED = 2
 MOE_VERIFY_STRICT = 4
+MOE_DRAFT_OK, MOE_DRAFT_TIMED_OUT = 0, 1
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_MISSING_EXPERT = 0, -1, -2, -3, -4
 
 EXPORTS = [
     "moe_create", "moe_destroy", "moe_status_string", "moe_last_hip_error", "moe_validate_desc",
     "moe_draft_call_fits",
     "moe_bf16_expert_bytes", "moe_int4_expert_q_bytes", "moe_int4_expert_sz_bytes",
-    "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init", "moe_route_topk",
+    "moe_int4_expert_scale_bytes", "moe_workspace_bytes", "moe_workspace_init",
+    "moe_workspace_idle_bytes", "moe_set_draft_spin_limit", "moe_draft_status", "moe_route_topk",
     "moe_draft_layer_int4", "moe_noalloc_scratch_bytes", "moe_draft_layer_int4_noalloc",
     "moe_prefill_workspace_bytes", "moe_draft_prefill_int4", "moe_expert_union",
     "moe_verify_layer_bf16", "moe_expert_copy_async",
@@ -85,6 +87,9 @@ def load_library():
             getattr(L, n).argtypes = [dp]; getattr(L, n).restype = sz
         L.moe_workspace_bytes.argtypes = [dp, i32, ctypes.POINTER(sz)]
         L.moe_workspace_init.argtypes = [vp, vp, sz, vp]
+        L.moe_workspace_idle_bytes.argtypes = [dp, ctypes.POINTER(sz)]
+        L.moe_set_draft_spin_limit.argtypes = [vp, ctypes.c_uint32]
+        L.moe_draft_status.argtypes = [vp, vp, sz, ctypes.POINTER(ctypes.c_int32), vp]
         L.moe_route_topk.argtypes = [vp, dp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_draft_layer_int4.argtypes = [vp, dp, vp, vp, vp, ctypes.POINTER(Int4Experts), vp, i32,
                                            vp, vp, vp, vp, sz, vp]
@@ -148,6 +153,14 @@ def workspace_bytes(desc: LayerDesc, max_tokens: int) -> int:
     return out.value
 
 
+def workspace_idle_bytes(desc: LayerDesc) -> int:
+    out = ctypes.c_size_t(0)
+    rc = load_library().moe_workspace_idle_bytes(ctypes.byref(desc), ctypes.byref(out))
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_workspace_idle_bytes")
+    return out.value
+
+
 def noalloc_scratch_bytes() -> int:
     return load_library().moe_noalloc_scratch_bytes()
 
@@ -204,6 +217,15 @@ class Context:
         self._check(self._lib.moe_workspace_init(self._h, _ptr(workspace),
                                                  workspace.numel() * workspace.element_size(),
                                                  _stream(stream)), "moe_workspace_init")
+
+    def set_draft_spin_limit(self, polls: int):
+        self._check(self._lib.moe_set_draft_spin_limit(self._h, polls), "moe_set_draft_spin_limit")
+
+    def draft_status(self, workspace, stream=None) -> int:
+        out = ctypes.c_int32(-1)
+        self._check(self._lib.moe_draft_status(self._h, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                               ctypes.byref(out), _stream(stream)), "moe_draft_status")
+        return out.value
 
     def route_topk(self, desc, x, w_router, router_bias, T, topk_ids, topk_w, topk_conf=None,
                    counts=None, offsets=None, perm=None, stream=None):

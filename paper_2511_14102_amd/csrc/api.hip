@@ -11,6 +11,7 @@ struct moe_ctx {
     int device;
     int n_cu;
     void *scratch;          // this device's address of the static scratch array
+    uint32_t spin_limit;    // polls of the router result before a draft workgroup gives up
     char arch[64];
     char hip_error[128];
     bool profiling;
@@ -136,6 +137,7 @@ int moe_create(moe_ctx **out, int device)
     c->profiling = false;
     c->device = device;
     c->n_cu = prop.multiProcessorCount;
+    c->spin_limit = kDefaultSpinLimit;
     {
         int prev = 0;
         hipError_t e = hipGetDevice(&prev);
@@ -266,12 +268,38 @@ int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *byte
     return MOE_OK;
 }
 
+int moe_workspace_idle_bytes(const moe_layer_desc *desc, size_t *bytes)
+{
+    if (!bytes || check_desc(desc) != MOE_OK) return MOE_ERR_INVALID_ARG;
+    *bytes = ws_layout(*desc, 1).plan;          // counters, status word and router-exchange slots
+    return MOE_OK;
+}
+
 int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < 256 || workspace_bytes % 4)
         return MOE_ERR_INVALID_ARG;
     launch_zero(workspace, workspace_bytes, (hipStream_t)stream);
     return hip_status(ctx, hipGetLastError());
+}
+
+int moe_set_draft_spin_limit(moe_ctx *ctx, uint32_t polls)
+{
+    if (!ctx || polls < 1) return MOE_ERR_INVALID_ARG;
+    ctx->spin_limit = polls;
+    return MOE_OK;
+}
+
+int moe_draft_status(moe_ctx *ctx, const void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
+{
+    if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < 256 || !status) return MOE_ERR_INVALID_ARG;
+    uint32_t word = 0;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(&word, (const char *)workspace + kWsStatusOffset, sizeof word, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return hip_status(ctx, e);
+    *status = word == 0 ? MOE_DRAFT_OK : MOE_DRAFT_TIMED_OUT;
+    return MOE_OK;
 }
 
 int moe_route_topk(moe_ctx *ctx, const moe_layer_desc *desc,
@@ -334,8 +362,13 @@ static int enqueue_draft(moe_ctx *ctx, const moe_layer_desc *desc, const void *x
     a.slots = (unsigned long long *)(ws + L.slots);
     a.replica_stride = L.slot_replica_bytes / 8;
     a.tickets = (uint32_t *)(ws + L.tickets);
+    a.status = (uint32_t *)(ws + L.tickets + kWsStatusOffset);
+    a.spin_limit = ctx->spin_limit;
     a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
     a.plan = plan; a.shared = shared; a.shared_stride = moe_bf16_expert_bytes(desc);
+    // the workgroups that reduce the router rows (the first min(E, grid) of the launch) must be
+    // running while the others wait for them
+    if (!draft_producers_resident(s, a, ctx->n_cu)) return MOE_ERR_INVALID_ARG;
     if (!timed) {
         launch_draft_fused(s, a, ctx->n_cu, st);
         if (s.S > 0) {
@@ -555,7 +588,7 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     a.missing = missing; a.n_missing = n_missing;
     // router and plan in one launch; its arrival counter sits behind the draft kernel's tickets
     { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
-      launch_route_plan(s, x, wr, bias, a, (uint32_t *)(ws + L.tickets + 128), st); }
+      launch_route_plan(s, x, wr, bias, a, (uint32_t *)(ws + L.tickets + kWsArrivalsOffset), st); }
     const int nexp = s.S + (s.E < s.T * s.k ? s.E : s.T * s.k);
     { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st); launch_bf16_gateup(s, plan, 0, nexp, x, ws + L.hb, nullptr, st); }
     { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);

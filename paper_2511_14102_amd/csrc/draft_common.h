@@ -25,7 +25,6 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
-constexpr uint32_t kSpinLimit = 1u << 22;
 // The router result is published in kReplicas copies; workgroup b polls copy b % kReplicas, so
 // that the polls of hundreds of workgroups do not all land on one address.
 constexpr int kReplicas = kDraftSlotReplicas;
@@ -102,6 +101,8 @@ struct FusedArgs {
     unsigned long long *slots;  // kReplicas x [T,E] x {logit bits, tag}; idle: tag = 0
     size_t replica_stride;      // in 8-byte units
     uint32_t *tickets;          // kTicketGroups + 1 counters; idle: 0
+    uint32_t *status;           // set to 1 when a wait for the router result ran out of polls
+    uint32_t spin_limit;        // polls of the router result before a workgroup gives up
     float *y;                   // [T,H] out, accumulated with atomics
     int32_t *ids_out;           // [T,k]
     float *conf_out;            // [T,k] or null
@@ -158,12 +159,24 @@ void launch_with_lds(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st
     launch(kernel, grid, block, lds, st, x, a);
 }
 
+// workgroups of `kernel` (block threads, lds bytes of dynamic LDS) one compute unit holds at once
+template <typename K>
+int resident_per_cu(K kernel, int threads, size_t lds)
+{
+    if (lds > 48 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, threads, lds) != hipSuccess) return 0;
+    return n;
+}
+
 inline FusedArgs fused_args(const Shape &s, const DraftFusedArgs &d)
 {
     FusedArgs a;
     a.wr = (const uint16_t *)d.wr; a.bias = d.bias;
     a.q = (const char *)d.q; a.sz = (const char *)d.sz; a.stride_q = d.stride_q; a.stride_sz = d.stride_sz;
     a.slots = d.slots; a.replica_stride = d.replica_stride; a.tickets = d.tickets; a.y = d.y;
+    a.status = d.status; a.spin_limit = d.spin_limit;
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
     a.items = d.items; a.n_items = d.n_items; a.sorted = d.sorted; a.w_all = d.w_all;

@@ -356,7 +356,7 @@ void draft_stream_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         {
             uint32_t spins = 0;
             bool all = false;
-            while (!all && ++spins < kSpinLimit) {
+            while (!all && ++spins < a.spin_limit) {
                 bool mine = true;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -373,7 +373,13 @@ void draft_stream_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 all = __all(mine);
                 if (!all) __builtin_amdgcn_s_sleep(2);
             }
-            if (!all) { if (lane == 0) s_flag = 0; continue; }
+            if (!all) {                          // gave up: the call fails, and says so in the workspace
+                if (lane == 0) {
+                    s_flag = 0;
+                    __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                continue;
+            }
         }
         STAMP(2);
 #pragma unroll
@@ -923,6 +929,34 @@ void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, int n_cu, hipSt
     const uint16_t *x = (const uint16_t *)d.x;
     if (d.symmetric) launch_stream<true>(s.T, x, a, n_cu, st);
     else launch_stream<false>(s.T, x, a, n_cu, st);
+}
+
+template <int MT, bool SYM>
+int stream_resident_per_cu(const Shape &s)
+{
+    constexpr int NW = stream_waves(MT), KW = stream_window(MT);
+    const size_t lds = draft_dynamic_lds(MT, s.H, s.g, s.E, SYM);
+    if (s.g == 32) return resident_per_cu(draft_stream_kernel<MT, 1, SYM, NW, KW>, NW * 64, lds);
+    if (s.g == 64) return resident_per_cu(draft_stream_kernel<MT, 2, SYM, NW, KW>, NW * 64, lds);
+    return resident_per_cu(draft_stream_kernel<MT, 4, SYM, NW, KW>, NW * 64, lds);
+}
+
+// The launch shapes: one token, one workgroup per item, dispatched in order, so the first
+// min(E, grid) of them are resident together when that many fit on the device at once; more tokens,
+// a grid of at most stream_wg_per_cu workgroups per compute unit, all of which must fit at once.
+bool draft_producers_resident(const Shape &s, const DraftFusedArgs &d, int n_cu)
+{
+    const int maxu = s.E < s.T * s.k ? s.E : s.T * s.k;
+    const long items = (long)maxu * (s.I / 32);
+    if (s.T == 1) {
+        const long need = s.E < items ? s.E : items;
+        return need <= draft_one_token_resident(s, d, n_cu);
+    }
+    const int MT = s.T <= 2 ? 2 : (s.T <= 4 ? 4 : 8);
+    int per = 0;
+    if (d.symmetric) per = MT == 2 ? stream_resident_per_cu<2, true>(s) : (MT == 4 ? stream_resident_per_cu<4, true>(s) : stream_resident_per_cu<8, true>(s));
+    else per = MT == 2 ? stream_resident_per_cu<2, false>(s) : (MT == 4 ? stream_resident_per_cu<4, false>(s) : stream_resident_per_cu<8, false>(s));
+    return per >= stream_wg_per_cu(MT);
 }
 
 bool draft_fits(const Shape &s, int tokens, bool sym)

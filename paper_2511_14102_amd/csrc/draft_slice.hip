@@ -148,7 +148,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         {
             uint32_t spins = 0;
             bool all = false;
-            while (!all && ++spins < kSpinLimit) {
+            while (!all && ++spins < a.spin_limit) {
                 bool mine = true;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -165,7 +165,13 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 all = __all(mine);
                 if (!all) __builtin_amdgcn_s_sleep(2);
             }
-            if (!all) { if (lane == 0) s_flag = 0; continue; }
+            if (!all) {                          // gave up: the call fails, and says so in the workspace
+                if (lane == 0) {
+                    s_flag = 0;
+                    __hip_atomic_store(a.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                continue;
+            }
         }
         if (E <= kLoneWaveTopk) {
             // Rank of every logit in the strict order (larger first, lower index first among equals),
@@ -766,6 +772,23 @@ void launch_draft_one_token(const Shape &s, const DraftFusedArgs &d, hipStream_t
     const int experts = a.E < a.k ? a.E : a.k;
     if (d.symmetric) launch_slice_t<1, true, false>(x, a, st, experts);
     else launch_slice_t<1, false, false>(x, a, st, experts);
+}
+
+int draft_one_token_resident(const Shape &s, const DraftFusedArgs &d, int n_cu)
+{
+    const size_t lds = slice_dynamic_lds(1, s.H, s.g, s.E, true);
+    int per = 0;
+    auto ask = [&](auto kernel) { per = resident_per_cu(kernel, kThreads, lds); };
+    if (d.symmetric) {
+        if (s.g == 32) ask(draft_fused_kernel<1, 1, true, false>);
+        else if (s.g == 64) ask(draft_fused_kernel<1, 2, true, false>);
+        else ask(draft_fused_kernel<1, 4, true, false>);
+    } else {
+        if (s.g == 32) ask(draft_fused_kernel<1, 1, false, false>);
+        else if (s.g == 64) ask(draft_fused_kernel<1, 2, false, false>);
+        else ask(draft_fused_kernel<1, 4, false, false>);
+    }
+    return per * n_cu;
 }
 
 bool draft_one_token_fits(const Shape &s)

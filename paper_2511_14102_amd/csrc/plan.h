@@ -62,6 +62,10 @@ struct Shape {
 // zero between calls ("idle state"): moe_workspace_init establishes it, the draft kernel
 // restores it.  Their sizes do not depend on T, so the idle region is the same for every call.
 constexpr int kDraftSlotReplicas = 16;   // copies of the draft kernel's router-exchange slots
+// inside the first 256 bytes (the `tickets` block): the verify call's arrival counter and the
+// draft calls' status word (0: fine, 1: a wait for the router result ran out of polls)
+constexpr size_t kWsArrivalsOffset = 128, kWsStatusOffset = 192;
+constexpr uint32_t kDefaultSpinLimit = 1u << 22;
 
 struct WsLayout {
     // tickets: one counter; slots: [MOE_MAX_DRAFT_TOKENS, E] x {fp64 logit, 64-bit tag} of the
@@ -111,6 +115,7 @@ struct DraftFusedArgs {
     const void *q, *sz; size_t stride_q, stride_sz;
     int symmetric;                     // sz holds scale blobs (z = 8)
     unsigned long long *slots; size_t replica_stride; uint32_t *tickets;
+    uint32_t *status; uint32_t spin_limit;
     float *y; int32_t *ids_out; float *conf_out;
     Plan *plan; const void *shared; size_t shared_stride;
     const PrefillItem *items; const int32_t *n_items; const int32_t *sorted; const float *w_all;   // prerouted only
@@ -119,6 +124,9 @@ struct DraftFusedArgs {
 void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, int n_cu, hipStream_t st);
 // whether the x copy and the entry buffers of a call with `tokens` tokens (1-8) fit into LDS
 bool draft_fits(const Shape &s, int tokens, bool symmetric);
+// whether the workgroups of the call's launch that reduce the router rows are all resident at once
+// (occupancy of the kernel the call will run x compute units)
+bool draft_producers_resident(const Shape &s, const DraftFusedArgs &a, int n_cu);
 // draft_slice.hip: one workgroup per (expert, slice) work item
 // grid sized for max_items work items; y must have been cleared
 void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &a, int max_items, hipStream_t st);
@@ -126,6 +134,7 @@ bool draft_prefill_fits(const Shape &s);
 // the call with ONE token (router inside the launch)
 void launch_draft_one_token(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
 bool draft_one_token_fits(const Shape &s);
+int draft_one_token_resident(const Shape &s, const DraftFusedArgs &a, int n_cu);   // workgroups resident at once
 void launch_zero(void *p, size_t bytes, hipStream_t st);
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st);
 

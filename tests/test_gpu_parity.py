@@ -495,3 +495,58 @@ def test_mixed_token_counts_share_one_workspace(ctx, tiny):
             torch.cuda.synchronize()
             assert np.array_equal(to_np(r["ids"]), ref["ids"]), (it, T)
             assert rel_err(to_np(r["y"]), ref["y"]) <= TOL_VERIFY, (it, T)
+
+
+def test_workspace_is_idle_again_after_every_call(ctx, tiny):
+    """The contract of moe_workspace_init: counters, status word and the tags of the exchange slots are
+    zero whenever no call runs, after draft calls of every launch shape and after verify calls."""
+    D, cfg = tiny.D, tiny.cfg
+    n = B.workspace_idle_bytes(D.desc)
+    assert 256 < n < D.workspace.numel()
+    x = tokens_with_clear_routing(cfg, tiny.A, 8, step=77)
+
+    def idle():
+        head = int(D.workspace[:256].count_nonzero().item())
+        tags = D.workspace[256:n].view(torch.int64).reshape(-1, 2)[:, 1]      # 16-byte slots: {logit, tag}
+        return head == 0 and int(tags.count_nonzero().item()) == 0
+    for T in (1, 2, 5, 8):
+        D.draft(x[:T].cuda())
+        torch.cuda.synchronize()
+        assert idle(), ("draft", T)
+        D.verify(x[:T].cuda())
+        torch.cuda.synchronize()
+        assert idle(), ("verify", T)
+    assert ctx.draft_status(D.workspace) == B.MOE_DRAFT_OK
+
+
+@pytest.mark.parametrize("name", ["tiny", "qwen3"])
+def test_draft_wait_that_runs_out_is_reported(ctx, name):
+    """The bounded wait for the router result, forced to give up from the host (one poll allowed, and
+    the loop tests the limit before it polls): every kernel still ends, ids are -1, the status word says
+    so, and after moe_workspace_init the workspace serves correct calls again."""
+    cfg = synth.config_by_name(name)
+    L = build_layer(cfg)
+    A = oracle_arrays(L)
+    D = DeviceLayer(ctx, cfg, L, max_tokens=8, verify=False)
+    x = tokens_with_clear_routing(cfg, A, 4, step=31)
+    try:
+        for T in (1, 4):
+            ctx.set_draft_spin_limit(1)
+            say("forced time-out", name, "T", T)
+            r = D.draft(x[:T].cuda())
+            torch.cuda.synchronize()                                   # the launch ended by itself
+            assert ctx.draft_status(D.workspace) == B.MOE_DRAFT_TIMED_OUT
+            assert bool((r["ids"] == -1).all()) and bool((r["conf"] == 0).all())
+            ctx.set_draft_spin_limit(1 << 22)
+            ctx.workspace_init(D.workspace)
+            assert ctx.draft_status(D.workspace) == B.MOE_DRAFT_OK
+            ref = oracle_draft(A, x[:T])
+            r = D.draft(x[:T].cuda())
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(r["ids"]), ref["ids"])
+            assert rel_err(to_np(r["y"]), ref["y"]) <= TOL_DRAFT
+            assert ctx.draft_status(D.workspace) == B.MOE_DRAFT_OK
+    finally:
+        ctx.set_draft_spin_limit(1 << 22)
+    with pytest.raises(B.MoeError):
+        ctx.set_draft_spin_limit(0)
