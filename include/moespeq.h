@@ -159,14 +159,14 @@ int moe_workspace_bytes(const moe_layer_desc *desc, int max_tokens, size_t *byte
 /* Puts a workspace into its idle state (enqueues a fill kernel on `stream`; workspace_bytes a
  * multiple of 4).  Required once after allocation, before the first moe_draft_layer_int4 OR
  * moe_verify_layer_bf16 call on it, and again after a draft call that timed out (below).  The first
- * 256 bytes and the slot area behind them hold what the kernels exchange between their workgroups:
+ * 512 bytes and the slot area behind them hold what the kernels exchange between their workgroups:
  * the draft kernels' ticket counters and tagged router-result slots, the verify call's arrival
- * counter, and the draft status word.  Both calls expect the counters and tags zero on entry and
+ * counters, and the draft status word.  Both calls expect the counters and tags zero on entry and
  * leave them zero on exit (also when the call is replayed from a HIP graph); nothing else is
  * carried from call to call. */
 int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream);
 
-/* Size of the leading part of a workspace that holds the "idle state": 256 bytes of counters and
+/* Size of the leading part of a workspace that holds the "idle state": 512 bytes of counters and
  * the status word, all zero whenever no call is running, then 16-byte router-exchange slots
  * {8 bytes of logit, 8 bytes of tag} whose tags are zero then.  It does not depend on the token
  * count. */

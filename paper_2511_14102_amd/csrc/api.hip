@@ -35,11 +35,12 @@ WsLayout ws_layout(const moe_layer_desc &d, int T)
     WsLayout L;
     const size_t n = (size_t)T * d.top_k, rows = n + (size_t)T * d.n_shared;
     size_t o = 0;
-    L.tickets = o; o += 256;
+    L.tickets = o; o += kWsHeadBytes;
     // replicas are skewed by 256 bytes so that they do not all map to the same memory channel
     L.slot_replica_bytes = align256((size_t)MOE_MAX_DRAFT_TOKENS * d.n_experts * 16) + 256;
     L.slots = o;   o += kDraftSlotReplicas * L.slot_replica_bytes;
     L.plan = o;   o += align256(sizeof(Plan));
+    L.vlogits = o; o += align256((size_t)MOE_MAX_TOKENS * d.n_experts * 8);   // verify router: fp64 logits [T, E]
     L.hb = o;     o += align256(rows * d.inter * 2);
     L.hb_lo = o;  o += align256(rows * d.inter * 2);
     L.obuf = o;   o += align256(rows * d.hidden * 4);
@@ -277,7 +278,7 @@ int moe_workspace_idle_bytes(const moe_layer_desc *desc, size_t *bytes)
 
 int moe_workspace_init(moe_ctx *ctx, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < 256 || workspace_bytes % 4)
+    if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < kWsHeadBytes || workspace_bytes % 4)
         return MOE_ERR_INVALID_ARG;
     launch_zero(workspace, workspace_bytes, (hipStream_t)stream);
     return hip_status(ctx, hipGetLastError());
@@ -292,7 +293,7 @@ int moe_set_draft_spin_limit(moe_ctx *ctx, uint32_t polls)
 
 int moe_draft_status(moe_ctx *ctx, const void *workspace, size_t workspace_bytes, int32_t *status, void *stream)
 {
-    if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < 256 || !status) return MOE_ERR_INVALID_ARG;
+    if (!ctx || !workspace || !aligned(workspace, 256) || workspace_bytes < kWsHeadBytes || !status) return MOE_ERR_INVALID_ARG;
     uint32_t word = 0;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(&word, (const char *)workspace + kWsStatusOffset, sizeof word, hipMemcpyDeviceToHost, st);
@@ -588,7 +589,9 @@ int moe_verify_layer_bf16(moe_ctx *ctx, const moe_layer_desc *desc,
     a.missing = missing; a.n_missing = n_missing;
     // router and plan in one launch; its arrival counter sits behind the draft kernel's tickets
     { ProfScope p(ctx, MOE_KERNEL_ROUTE, st);
-      launch_route_plan(s, x, wr, bias, a, (uint32_t *)(ws + L.tickets + kWsArrivalsOffset), st); }
+      launch_route_plan(s, x, wr, bias, a, (double *)(ws + L.vlogits),
+                        (uint32_t *)(ws + L.tickets + kWsTokenArrivalsOffset),
+                        (uint32_t *)(ws + L.tickets + kWsArrivalsOffset), st); }
     const int nexp = s.S + (s.E < s.T * s.k ? s.E : s.T * s.k);
     { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st); launch_bf16_gateup(s, plan, 0, nexp, x, ws + L.hb, nullptr, st); }
     { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);

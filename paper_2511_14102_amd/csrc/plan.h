@@ -62,16 +62,18 @@ struct Shape {
 // zero between calls ("idle state"): moe_workspace_init establishes it, the draft kernel
 // restores it.  Their sizes do not depend on T, so the idle region is the same for every call.
 constexpr int kDraftSlotReplicas = 16;   // copies of the draft kernel's router-exchange slots
-// inside the first 256 bytes (the `tickets` block): the verify call's arrival counter and the
+// inside the first block (the `tickets` block, kWsHeadBytes): the verify call's arrival counter and the
 // draft calls' status word (0: fine, 1: a wait for the router result ran out of polls)
 constexpr size_t kWsArrivalsOffset = 128, kWsStatusOffset = 192;
+constexpr size_t kWsTokenArrivalsOffset = 256;           // MOE_MAX_TOKENS counters of the verify call's router
+constexpr size_t kWsHeadBytes = 512;                     // size of that first block
 constexpr uint32_t kDefaultSpinLimit = 1u << 22;
 
 struct WsLayout {
     // tickets: one counter; slots: [MOE_MAX_DRAFT_TOKENS, E] x {fp64 logit, 64-bit tag} of the
     // draft kernel's router exchange; hb / hb_lo: bf16 intermediate and its bf16 remainder;
     // obuf: fp32 [rows,H] expert outputs
-    size_t tickets, slots, slot_replica_bytes, plan, hb, hb_lo, obuf, total;
+    size_t tickets, slots, slot_replica_bytes, plan, vlogits, hb, hb_lo, obuf, total;
 };
 WsLayout ws_layout(const moe_layer_desc &d, int max_tokens);
 
@@ -92,9 +94,10 @@ struct PlanArgs {
     int32_t *missing; int32_t *n_missing;
 };
 void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st);
-// router + plan in one launch; arrivals: 4-byte counter in the workspace, zero between launches
+// router + plan in one launch; logits: [T, E] fp64 scratch; token_arrivals [MOE_MAX_TOKENS] and
+// arrivals: counters in the workspace, zero between launches
 void launch_route_plan(const Shape &s, const void *x, const void *wr, const float *bias, const PlanArgs &a,
-                       uint32_t *arrivals, hipStream_t st);
+                       double *logits, uint32_t *token_arrivals, uint32_t *arrivals, hipStream_t st);
 // plan of the S shared experts alone over s.T tokens
 void launch_shared_plan(const Shape &s, Plan *plan, const void *shared, size_t shared_stride, hipStream_t st);
 struct PrefillItem;

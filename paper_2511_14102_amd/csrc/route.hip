@@ -367,22 +367,115 @@ void plan_kernel(const PlanKernelArgs a)
                      a.shared, a.shared_stride, a.flags, a.ids_out, a.conf_out, a.missing, a.n_missing);
 }
 
-// Router and plan in one launch (the verify call): one workgroup per token routes it and stores
-// ids / weights / confidences at agent scope, waits for its stores, and takes a number; the
-// workgroup that takes the last number has everybody's results in reach (agent-scope loads) and
-// builds the plan.  `arrivals` is a counter in the workspace that is zero between launches.
+// Router and plan in one launch (the verify call).  Workgroup (b, t) reduces the router rows of
+// experts 16 b .. 16 b + 15 for token t, one row per wave, and stores the fp64 logits at agent
+// scope; the workgroup that arrives last for its token (a counter per token) has all of the
+// token's logits in reach, ranks them, forms the softmax weights and stores ids / weights /
+// confidences; the workgroup that arrives last of all builds the plan.  All counters live in the
+// workspace, are zero between launches and are put back to zero by the last arrival.  (One
+// workgroup per token computing all E rows took 25 us for 128 experts: the instruction rate of
+// the one compute unit a token ran on.)
+constexpr int kRouteBlock = kRouteThreads / 64;          // experts per workgroup: one per wave
+
 __global__ __launch_bounds__(kRouteThreads)
 void route_plan_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ wr,
                        const float *__restrict__ bias, int H, int renorm, const PlanKernelArgs a,
-                       uint32_t *arrivals)
+                       double *logits, uint32_t *token_arrivals, uint32_t *arrivals)
 {
+    __shared__ double s_logit[MOE_MAX_EXPERTS];
+    __shared__ int32_t s_rank[MOE_MAX_EXPERTS];
     __shared__ int s_last;
-    route_token<true>(x, wr, bias, H, a.E, a.k, renorm, a.plan->ids, a.plan->w, a.plan->conf);
+    const int t = blockIdx.y, E = a.E, k = a.k;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nblk = gridDim.x;
+    const int e = blockIdx.x * kRouteBlock + wave;
+    if (e < E) {
+        const uint16_t *xt = x + (size_t)t * H, *row = wr + (size_t)e * H;
+        // eight independent partial sums instead of one chain of dependent fp64 additions; the
+        // products are exact in fp32 (bf16 x bf16)
+        double part[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+        for (int c = lane; c < H / 8; c += 64) {
+            uint4 xv = *reinterpret_cast<const uint4 *>(xt + c * 8);
+            uint4 wv = *reinterpret_cast<const uint4 *>(row + c * 8);
+            const uint32_t xs[4] = {xv.x, xv.y, xv.z, xv.w};
+            const uint32_t ws[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                part[2 * i] += (double)(__uint_as_float(xs[i] << 16) * __uint_as_float(ws[i] << 16));
+                part[2 * i + 1] += (double)(__uint_as_float(xs[i] & 0xffff0000u) * __uint_as_float(ws[i] & 0xffff0000u));
+            }
+        }
+        double acc = ((part[0] + part[1]) + (part[2] + part[3])) + ((part[4] + part[5]) + (part[6] + part[7]));
+        acc = wave::sum(acc);
+        if (lane == 0) {
+            acc += bias ? (double)bias[e] : 0.0;
+            if (nblk > 1) __hip_atomic_store(&logits[(size_t)t * E + e], acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else { s_logit[e] = acc; s_rank[e] = 0; }
+        }
+    }
+    if (nblk > 1) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this thread's stores have been performed
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t n = __hip_atomic_fetch_add(&token_arrivals[t], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = n == (uint32_t)nblk - 1;
+            if (s_last) __hip_atomic_store(&token_arrivals[t], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!s_last) return;
+        for (int i = threadIdx.x; i < E; i += kRouteThreads) {
+            s_logit[i] = __hip_atomic_load(&logits[(size_t)t * E + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_rank[i] = 0;
+        }
+    }
+    __syncthreads();
+    // Rank of every logit under (larger first, lower index first among equals), counted by all
+    // sixteen waves, each over its share of the experts; the order is strict, so the ranks are a
+    // permutation and rank < k is the selection.
+    wave::count_ranks(s_logit, s_rank, E, lane, wave, kRouteThreads / 64);
+    __syncthreads();
+    if (wave == 0) {
+        double mine[4], pe[4];
+        int rank[4];
+        double mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ei = lane + 64 * i;
+            const bool have = 64 * i < E && ei < E;
+            mine[i] = have ? s_logit[ei] : -INFINITY;
+            rank[i] = have ? s_rank[ei] : MOE_MAX_EXPERTS;
+            mx = fmax(mx, mine[i]);
+        }
+        mx = wave::max(mx);
+        double den = 0.0, sel = 0.0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pe[i] = rank[i] < MOE_MAX_EXPERTS ? exp(mine[i] - mx) : 0.0;
+            den += pe[i];
+        }
+        den = wave::sum(den);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pe[i] = pe[i] / den;
+            sel += rank[i] < k ? pe[i] : 0.0;
+        }
+        sel = wave::sum(sel);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (rank[i] < k) {
+                const size_t o = (size_t)t * k + rank[i];
+                put<true>(&a.plan->ids[o], (int32_t)(lane + 64 * i));
+                const float c = (float)pe[i];
+                put<true>(&a.plan->conf[o], c);
+                put<true>(&a.plan->w[o], renorm ? (float)(pe[i] / sel) : c);
+            }
+        }
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this thread's stores have been performed
     __syncthreads();
     if (threadIdx.x == 0) {
         const uint32_t n = __hip_atomic_fetch_add(arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = n == gridDim.x - 1;
+        s_last = n == gridDim.y - 1;
         if (s_last) __hip_atomic_store(arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
@@ -456,10 +549,11 @@ void launch_plan(const Shape &s, const PlanArgs &a, hipStream_t st)
 }
 
 void launch_route_plan(const Shape &s, const void *x, const void *wr, const float *bias, const PlanArgs &a,
-                       uint32_t *arrivals, hipStream_t st)
+                       double *logits, uint32_t *token_arrivals, uint32_t *arrivals, hipStream_t st)
 {
-    launch(route_plan_kernel, dim3(s.T), dim3(kRouteThreads), 0, st, (const uint16_t *)x, (const uint16_t *)wr,
-           bias, s.H, s.renorm, plan_kernel_args(s, a), arrivals);
+    const dim3 grid((s.E + kRouteBlock - 1) / kRouteBlock, s.T);
+    launch(route_plan_kernel, grid, dim3(kRouteThreads), 0, st, (const uint16_t *)x, (const uint16_t *)wr,
+           bias, s.H, s.renorm, plan_kernel_args(s, a), logits, token_arrivals, arrivals);
 }
 
 void launch_shared_plan(const Shape &s, Plan *plan, const void *shared, size_t shared_stride, hipStream_t st)

@@ -502,12 +502,12 @@ def test_workspace_is_idle_again_after_every_call(ctx, tiny):
     zero whenever no call runs, after draft calls of every launch shape and after verify calls."""
     D, cfg = tiny.D, tiny.cfg
     n = B.workspace_idle_bytes(D.desc)
-    assert 256 < n < D.workspace.numel()
+    assert 512 < n < D.workspace.numel()
     x = tokens_with_clear_routing(cfg, tiny.A, 8, step=77)
 
     def idle():
-        head = int(D.workspace[:256].count_nonzero().item())
-        tags = D.workspace[256:n].view(torch.int64).reshape(-1, 2)[:, 1]      # 16-byte slots: {logit, tag}
+        head = int(D.workspace[:512].count_nonzero().item())
+        tags = D.workspace[512:n].view(torch.int64).reshape(-1, 2)[:, 1]      # 16-byte slots: {logit, tag}
         return head == 0 and int(tags.count_nonzero().item()) == 0
     for T in (1, 2, 5, 8):
         D.draft(x[:T].cuda())
