@@ -66,7 +66,11 @@ def roofline_table(cfg, kern, nbytes, root):
         ach = nbytes[name] / (kk["us_avg"] * 1e-6) / 1e9
         table[name] = {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                        "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                       "traffic": traffic.get(name), "bytes_per_launch": int(nbytes[name]),
+                       "traffic": traffic.get(name),
+                       "traffic_source": "profiles/pmc_traffic.json: fabric-side FETCH_SIZE + WRITE_SIZE per launch from "
+                                         "committed rocprofv3 --pmc runs of this command, not measured in this run"
+                                         if traffic.get(name) else None,
+                       "bytes_per_launch": int(nbytes[name]),
                        "us_per_launch": round(kk["us_avg"], 2), "launches": kk["launches"],
                        "ms_total": round(kk["ms_total"], 3)}
     dominant = max(table.values(), key=lambda r: r["ms_total"]) if table else None   # most time in the timed region
@@ -79,23 +83,33 @@ def read_profile(ctx):
 
 
 def cpu_baseline(cfg, L0, K, T):
-    """The oracle as it stands on layer 0's step, for at least 10 s of host work."""
+    """The oracle as it stands on layer 0's step: about 10 s of host work on all threads the process
+    has, then a few steps on one thread."""
     import synth
     from oracle import oracle as orc
-    from tests.common import oracle_arrays, oracle_draft, oracle_verify
+    from oracle.layer_check import oracle_arrays, oracle_draft, oracle_verify
     A = oracle_arrays(L0)
-    tc = time.time()
-    reps = 0
-    while time.time() - tc < 10.0 and reps < 64:
-        x0 = synth.make_tokens(cfg, T, layer=0, step=reps)
-        oracle_draft(A, x0[:K])
-        oracle_verify(A, x0)
-        reps += 1
-    dt = time.time() - tc
-    return {"value": round(reps * (2 * K + 1) / dt, 3), "unit": "tokens/s", "cores": orc.num_threads(),
+
+    def run(budget_s, max_reps):
+        tc = time.time()
+        reps = 0
+        while (time.time() - tc < budget_s and reps < max_reps) or reps == 0:
+            x0 = synth.make_tokens(cfg, T, layer=0, step=reps)
+            oracle_draft(A, x0[:K])
+            oracle_verify(A, x0)
+            reps += 1
+        return reps, time.time() - tc
+    threads = orc.num_threads()
+    reps, dt = run(10.0, 64)
+    orc.set_num_threads(1)
+    reps1, dt1 = run(4.0, 8)
+    orc.set_num_threads(threads)
+    return {"value": round(reps * (2 * K + 1) / dt, 3), "unit": "tokens/s", "cores": threads,
             "kind": "oracle", "seconds": round(dt, 2),
             "sample": "%d steps of layer 0 (fresh tokens each): %d draft tokens (int4) + one verify of %d "
-                      "tokens (bf16) per step" % (reps, K, T)}
+                      "tokens (bf16) per step" % (reps, K, T),
+            "single_thread": {"value": round(reps1 * (2 * K + 1) / dt1, 3), "unit": "tokens/s", "cores": 1,
+                              "seconds": round(dt1, 2), "steps": reps1}}
 
 
 def stream_ceiling(ctx, torch, blobs, nbytes, grid, reps=64):
@@ -187,17 +201,22 @@ def resident_leg(args, cfg, ctx, dev):
         ctx.expert_union(b["win"], K * k, E, D.slot_of_expert, b["mask"], b["lst"], b["nl"], b["miss"], b["nm"])
         D.verify(x, y=b["yv"], ids=b["idv"])
 
-    def timed(fn, n_warm, n_steps):
+    def timed(fn, n_warm, n_steps, passes=5):
+        """Median over `passes` timed passes of exactly n_steps steps each, after n_warm warm-up steps."""
         for i in range(n_warm):
             fn(i % n_layers)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(n_steps):
-            fn((n_warm + i) % n_layers)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n_steps
+        per_step = []
+        for p in range(passes):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(n_steps):
+                fn((n_warm + i) % n_layers)
+            e1.record()
+            torch.cuda.synchronize()
+            per_step.append(e0.elapsed_time(e1) / n_steps)
+        return float(np.median(per_step)), per_step
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
@@ -207,8 +226,8 @@ def resident_leg(args, cfg, ctx, dev):
         torch.cuda.synchronize()
         del src, dst
 
-    ms_eager = timed(step, args.warmup, args.steps)
-    log("eager: %.3f ms/step" % ms_eager)
+    ms_eager, passes_eager = timed(step, args.warmup, args.steps)
+    log("eager: %.3f ms/step (passes: %s)" % (ms_eager, " ".join("%.3f" % v for v in passes_eager)))
     ms_step, launch = ms_eager, "eager"
     if args.mode == "graph":
         graphs = []
@@ -219,22 +238,25 @@ def resident_leg(args, cfg, ctx, dev):
                 step(li)
             graphs.append(gph)
         torch.cuda.synchronize()
-        ms_graph = timed(lambda li: graphs[li].replay(), args.warmup, args.steps)
-        log("graph: %.3f ms/step" % ms_graph)
+        ms_graph, passes_graph = timed(lambda li: graphs[li].replay(), args.warmup, args.steps)
+        log("graph: %.3f ms/step (passes: %s)" % (ms_graph, " ".join("%.3f" % v for v in passes_graph)))
         if ms_graph < ms_eager:
             ms_step, launch = ms_graph, "hipgraph"
 
-    # ---- what the steps computed: distinct experts per verify call, from the ids
+    # ---- what the steps computed: distinct experts per verify call, from the ids of the layers the
+    # timed steps ran on (weighted by how often each ran)
     torch.cuda.synchronize()
-    uniq = [len(set(bufs[li]["idv"].cpu().numpy().reshape(-1).tolist())) for li in range(n_layers)]
-    mean_u = float(np.mean(uniq))
-    mean_u_run = float(np.mean([uniq[(args.warmup + i) % n_layers] for i in range(args.steps)]))
-    nbytes = algorithmic_bytes(cfg, T, mean_u_run, sym)
+    ran = [(args.warmup + i) % n_layers for i in range(args.steps)]
+    uniq = {li: len(set(bufs[li]["idv"].cpu().numpy().reshape(-1).tolist())) for li in sorted(set(ran))}
+    mean_u = float(np.mean([uniq[li] for li in ran]))
+    nbytes = algorithmic_bytes(cfg, T, mean_u, sym)
 
     # ---- per-kernel time (eager, event pairs around every kernel launch)
     roofline, extra = None, {}
     if sym:
         extra["int4_format"] = "symmetric (z = 8, scale blobs)"
+    extra["timing"] = {"passes": 5, "ms_per_step_each_pass": [round(v, 4) for v in (passes_graph if launch == "hipgraph" else passes_eager)],
+                       "reported": "median"}
     if args.mode == "graph":
         extra["ms_graph"] = round(ms_graph, 4)
     if not args.no_profile:
@@ -251,6 +273,18 @@ def resident_leg(args, cfg, ctx, dev):
         grid = k * cfg.inter // 32
         extra["stream_read_ceiling"] = stream_ceiling(ctx, torch, [D.q_blob for D in layers],
                                                       nbytes["draft_fused_kernel"], grid)
+        # the same draft call with the layer changing from call to call: no expert is read twice within
+        # the reach of the memory-side cache (in a step the K draft calls hit one layer, whose popular
+        # expert may be served from that cache)
+        ctx.profile_enable(True)
+        for i in range(4 * n_layers):
+            li = i % n_layers
+            layers[li].draft(xs[li][i % K:i % K + 1], y=bufs[li]["yd"][0:1], ids=bufs[li]["win"][0:1], conf=bufs[li]["conf"][0:1])
+        torch.cuda.synchronize()
+        rot = read_profile(ctx).get("draft_fused_kernel")
+        ctx.profile_enable(False)
+        if rot:
+            extra["draft_kernel_us_layer_rotating"] = round(rot["us_avg"], 2)
         extra["per_call"] = {
             "draft_us": round(kern["draft_fused_kernel"]["us_avg"], 2),
             "draft_tokens_per_s": round(1e6 / kern["draft_fused_kernel"]["us_avg"], 1),
@@ -261,7 +295,7 @@ def resident_leg(args, cfg, ctx, dev):
 
     # ---- layer 0's step as the timed launches left it, against the oracle (same buffers, same path)
     if not args.no_cpu_baseline:
-        from tests.common import oracle_arrays, oracle_draft, oracle_verify, rel_err
+        from oracle.layer_check import oracle_arrays, oracle_draft, oracle_verify, rel_err
         step(0)
         torch.cuda.synchronize()
         A0 = oracle_arrays(L0)
@@ -594,7 +628,7 @@ def offload_leg(args, cfg, ctx, dev):
 
     # ---- the last cycle's result on layer 0 against the oracle (same launch path as timed)
     if not args.no_cpu_baseline:
-        from tests.common import oracle_arrays, oracle_verify, rel_err
+        from oracle.layer_check import oracle_arrays, oracle_verify, rel_err
         ref = oracle_verify(oracle_arrays(L0), xs[last][0].cpu())
         err = rel_err(yv[0].float().cpu().numpy().astype(np.float64), ref["y"])
         assert np.array_equal(idv[0].cpu().numpy(), ref["ids"]) and err <= 2e-2, "layer 0 of the cycle disagrees with the oracle"

@@ -550,3 +550,70 @@ def test_draft_wait_that_runs_out_is_reported(ctx, name):
         ctx.set_draft_spin_limit(1 << 22)
     with pytest.raises(B.MoeError):
         ctx.set_draft_spin_limit(0)
+
+
+class Guarded:
+    """A device buffer with canary bytes before and after the part handed to the library."""
+    PAD = 4096
+
+    def __init__(self, nbytes, dtype=torch.uint8, shape=None):
+        self.raw = torch.full((nbytes + 2 * self.PAD,), 0xA5, dtype=torch.uint8, device="cuda")
+        self.view = self.raw[self.PAD:self.PAD + nbytes].view(dtype)
+        if shape is not None:
+            self.view = self.view.reshape(shape)
+
+    def intact(self):
+        n = self.raw.numel()
+        return bool((self.raw[:self.PAD] == 0xA5).all()) and bool((self.raw[n - self.PAD:] == 0xA5).all())
+
+
+@pytest.mark.parametrize("name", ["tiny", "s192"])
+def test_no_entry_point_writes_outside_its_outputs_or_workspace(ctx, name):
+    """Canary bytes around every output and around the workspace survive one call of every entry point
+    (a shape with a shared expert exercises the plan, intermediate and partial-output scratch)."""
+    from synth.configs import LayerConfig
+    cfg = synth.config_by_name("tiny") if name == "tiny" else LayerConfig(52, "s192", 192, 5, 128, 2, 64, 1, 1)
+    L = build_layer(cfg)
+    A = oracle_arrays(L)
+    D = DeviceLayer(ctx, cfg, L, max_tokens=8)
+    H, k, E = cfg.hidden, cfg.top_k, cfg.n_experts
+    ws = Guarded(D.workspace.numel())
+    ctx.workspace_init(ws.view)
+    D.workspace = ws.view
+    x = tokens_with_clear_routing(cfg, A, 8, step=5)
+    guards = [ws]
+
+    def out(T, cols, dtype):
+        g = Guarded(T * cols * torch.empty((), dtype=dtype).element_size(), dtype, (T, cols))
+        guards.append(g)
+        return g.view
+    for T in (1, 3, 8):
+        xd = x[:T].cuda()
+        ref_d, ref_v = oracle_draft(A, x[:T]), oracle_verify(A, x[:T])
+        r = D.draft(xd, y=out(T, H, torch.float32), ids=out(T, k, torch.int32), conf=out(T, k, torch.float32))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref_d["ids"]) and rel_err(to_np(r["y"]), ref_d["y"]) <= TOL_DRAFT
+        r = D.prefill(xd, y=out(T, H, torch.float32), ids=out(T, k, torch.int32), conf=out(T, k, torch.float32))
+        torch.cuda.synchronize()
+        assert rel_err(to_np(r["y"]), ref_d["y"]) <= TOL_DRAFT
+        D.missing, D.n_missing = out(1, E, torch.int32).reshape(-1), out(1, 1, torch.int32).reshape(-1)
+        r = D.verify(xd, y=out(T, H, torch.bfloat16), ids=out(T, k, torch.int32))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(r["ids"]), ref_v["ids"]) and rel_err(to_np(r["y"]), ref_v["y"]) <= TOL_VERIFY
+        ids, w, conf = out(T, k, torch.int32), out(T, k, torch.float32), out(T, k, torch.float32)
+        cnt, off, pm = out(1, E, torch.int32).reshape(-1), out(1, E + 1, torch.int32).reshape(-1), out(1, T * k, torch.int32).reshape(-1)
+        ctx.route_topk(D.desc, xd, D.router, D.bias, T, ids, w, conf, cnt, off, pm)
+        mask, lst, miss = out(1, (E + 63) // 64, torch.int64).reshape(-1), out(1, E, torch.int32).reshape(-1), out(1, E, torch.int32).reshape(-1)
+        nl, nm = out(1, 1, torch.int32).reshape(-1), out(1, 1, torch.int32).reshape(-1)
+        ctx.expert_union(ids.reshape(-1), T * k, E, D.slot_of_expert, mask, lst, nl, miss, nm)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(ids), ref_v["ids"])
+    # the prefill workspace is allocated by the harness; give it canaries too
+    pw = Guarded(B.prefill_workspace_bytes(D.desc, 40))
+    guards.append(pw)
+    D._prefill_ws = pw.view
+    xp = tokens_with_clear_routing(cfg, A, 40, step=6, kind="iid")
+    r = D.prefill(xp.cuda(), y=out(40, H, torch.float32), ids=out(40, k, torch.int32), conf=out(40, k, torch.float32))
+    torch.cuda.synchronize()
+    assert rel_err(to_np(r["y"]), oracle_draft(A, xp)["y"]) <= TOL_DRAFT
+    assert all(g.intact() for g in guards), [i for i, g in enumerate(guards) if not g.intact()]
