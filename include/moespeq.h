@@ -375,7 +375,11 @@ int moe_expert_copy_async(moe_ctx *ctx, void *dst_slot_dev, const void *src_pinn
 #define MOE_KERNEL_BF16_DOWN     5   /* bf16 down small-M contraction                        */
 #define MOE_KERNEL_COMBINE       6   /* weighted sum over a token's experts                  */
 #define MOE_KERNEL_UNION         7   /* expert union                                         */
-#define MOE_KERNEL_COUNT         8
+#define MOE_KERNEL_PREFILL_STAGE   8  /* moe_draft_prefill_int4: tokens gathered into operand tiles  */
+#define MOE_KERNEL_PREFILL_GATEUP  9  /* ... int4 gate+up grouped small-M contraction, SwiGLU         */
+#define MOE_KERNEL_PREFILL_DOWN    10 /* ... int4 down grouped small-M contraction                    */
+#define MOE_KERNEL_PREFILL_COMBINE 11 /* ... weighted sum over a token's experts                      */
+#define MOE_KERNEL_COUNT         12
 
 /* With profiling enabled, every kernel launch of moe_route_topk / moe_draft_layer_int4 /
  * moe_expert_union / moe_verify_layer_bf16 / moe_stream_read_probe carries a pair of HIP events

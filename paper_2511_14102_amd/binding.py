@@ -36,7 +36,7 @@ SCHED_EXPORTS = [
     "moe_cache_create", "moe_cache_destroy", "moe_cache_place", "moe_cache_slot_table", "moe_cache_use",
     "moe_cache_stats", "moe_cache_end_window", "moe_sched_plan", "moe_sched_on_demand",
 ]
-KERNEL_COUNT = 8
+KERNEL_COUNT = 12
 
 
 class MoeError(RuntimeError):

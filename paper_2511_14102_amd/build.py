@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoespeq.so")
-SOURCES = ["api.hip", "route.hip", "draft_int4.hip", "draft_slice.hip", "expert_bf16.hip", "governor.cpp", "scheduler.cpp"]   # .cpp: host code only
+SOURCES = ["api.hip", "route.hip", "draft_int4.hip", "draft_slice.hip", "draft_prefill.hip", "expert_bf16.hip", "governor.cpp", "scheduler.cpp"]   # .cpp: host code only
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU ops are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

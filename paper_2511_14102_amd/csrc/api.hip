@@ -209,7 +209,8 @@ const char *moe_kernel_name(int kernel)
 {
     static const char *names[MOE_KERNEL_COUNT] = {
         "route_kernel", "plan_kernel", "draft_fused_kernel", "stream_read_kernel",
-        "bf16_gateup_kernel", "bf16_down_kernel", "combine_kernel", "union_kernel"};
+        "bf16_gateup_kernel", "bf16_down_kernel", "combine_kernel", "union_kernel",
+        "prefill_stage_kernel", "prefill_gateup_kernel", "prefill_down_kernel", "prefill_combine_kernel"};
     return (kernel >= 0 && kernel < MOE_KERNEL_COUNT) ? names[kernel] : "";
 }
 
@@ -427,22 +428,35 @@ int moe_draft_layer_int4_noalloc(moe_ctx *ctx, const moe_layer_desc *desc,
     return enqueue_draft(ctx, desc, x, wr, bias, routed, shared, T, y, ids_out, conf_out, ws, L, st, false);
 }
 
-// workspace of a prefill call: routing weights and sorted assignment indices [T k], the item
-// count (one 256-byte line) and the items
+// workspace of a prefill call: routing weights, sorted assignment indices and slots [T k], the
+// item count (one 256-byte line), the items, the operand tiles of x and of h (two planes) with
+// their tile row sums, and the per-slot outputs.
 // With shared experts: two plans (full chunk, ragged last chunk) and the buffers of one chunk of
 // `chunk` tokens through the bf16 kernels.
-struct PrefillLayout { size_t w_all, sorted, n_items, items, plan_full, plan_tail, shared_ws, total; int max_items, chunk; };
+struct PrefillLayout {
+    size_t w_all, sorted, slot_of, n_items, items, xt, x_sums, h_hi, h_lo, h_sums, obuf,
+        plan_full, plan_tail, shared_ws, total;
+    int max_items, chunk;
+};
 static PrefillLayout prefill_layout(const moe_layer_desc &d, int T)
 {
     PrefillLayout L;
     const size_t n = (size_t)T * d.top_k;
     // sum over experts of ceil(count / chunk) <= n / chunk + number of experts that occur
     L.max_items = (int)(n / kPrefillChunk + ((size_t)d.n_experts < n ? (size_t)d.n_experts : n));
+    const PrefillBuffers B = prefill_buffers(d, L.max_items);
     size_t o = 0;
     L.w_all = o;   o += align256(n * 4);
     L.sorted = o;  o += align256(n * 4);
+    L.slot_of = o; o += align256(n * 4);
     L.n_items = o; o += 256;
     L.items = o;   o += align256((size_t)L.max_items * sizeof(PrefillItem));
+    L.xt = o;      o += align256(B.xt);
+    L.x_sums = o;  o += align256(B.x_sums);
+    L.h_hi = o;    o += align256(B.h_plane);
+    L.h_lo = o;    o += align256(B.h_plane);
+    L.h_sums = o;  o += align256(B.h_sums);
+    L.obuf = o;    o += align256(B.obuf);
     L.chunk = MOE_MAX_ASSIGN / d.top_k < MOE_MAX_TOKENS ? MOE_MAX_ASSIGN / d.top_k : MOE_MAX_TOKENS;
     L.plan_full = L.plan_tail = L.shared_ws = o;
     if (d.n_shared > 0) {
@@ -487,28 +501,30 @@ int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,
         routed->expert_stride_sz < sz_bytes)
         return MOE_ERR_INVALID_ARG;
     const Shape s = make_shape(desc, T);
-    if (!draft_prefill_fits(s)) return MOE_ERR_INVALID_ARG;
     const PrefillLayout L = prefill_layout(*desc, T);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < L.total) return MOE_ERR_WORKSPACE;
 
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
-    float *w_all = (float *)(ws + L.w_all);
-    int32_t *sorted = (int32_t *)(ws + L.sorted);
-    int32_t *n_items = (int32_t *)(ws + L.n_items);
-    PrefillItem *items = (PrefillItem *)(ws + L.items);
-    { ProfScope p(ctx, MOE_KERNEL_ROUTE, st); launch_route(s, x, wr, bias, ids_out, w_all, conf_out, st); }
-    launch_zero(y, (size_t)T * s.H * 4, st);
-    { ProfScope p(ctx, MOE_KERNEL_PLAN, st); launch_prefill_plan(ids_out, T * s.k, s.E, sorted, items, n_items, st); }
-    DraftFusedArgs a;
-    memset(&a, 0, sizeof a);
-    a.x = x; a.wr = wr; a.bias = bias;
-    a.q = routed->q; a.sz = routed->sz;
-    a.stride_q = routed->expert_stride_q; a.stride_sz = routed->expert_stride_sz;
-    a.symmetric = routed->symmetric ? 1 : 0;
-    a.y = y; a.ids_out = ids_out; a.conf_out = conf_out;
-    a.items = items; a.n_items = n_items; a.sorted = sorted; a.w_all = w_all;
-    { ProfScope p(ctx, MOE_KERNEL_DRAFT_FUSED, st); launch_draft_prerouted(s, a, L.max_items, st); }
+    PrefillCall p;
+    p.x = x; p.q = routed->q; p.sz = routed->sz;
+    p.stride_q = routed->expert_stride_q; p.stride_sz = routed->expert_stride_sz;
+    p.symmetric = routed->symmetric ? 1 : 0;
+    p.items = (const PrefillItem *)(ws + L.items); p.n_items = (const int32_t *)(ws + L.n_items);
+    p.sorted = (const int32_t *)(ws + L.sorted); p.slot_of = (const int32_t *)(ws + L.slot_of);
+    p.w_all = (const float *)(ws + L.w_all);
+    p.xt = ws + L.xt; p.x_sums = (float *)(ws + L.x_sums);
+    p.h_hi = ws + L.h_hi; p.h_lo = ws + L.h_lo; p.h_sums = (float *)(ws + L.h_sums);
+    p.obuf = (float *)(ws + L.obuf);
+    p.y = y;
+    { ProfScope t(ctx, MOE_KERNEL_ROUTE, st); launch_route(s, x, wr, bias, ids_out, (float *)(ws + L.w_all), conf_out, st); }
+    { ProfScope t(ctx, MOE_KERNEL_PLAN, st);
+      launch_prefill_plan(ids_out, T * s.k, s.E, (int32_t *)(ws + L.sorted), (int32_t *)(ws + L.slot_of),
+                          (PrefillItem *)(ws + L.items), (int32_t *)(ws + L.n_items), st); }
+    { ProfScope t(ctx, MOE_KERNEL_PREFILL_STAGE, st); launch_prefill_stage(s, p, L.max_items, st); }
+    { ProfScope t(ctx, MOE_KERNEL_PREFILL_GATEUP, st); launch_prefill_gateup(s, p, L.max_items, st); }
+    { ProfScope t(ctx, MOE_KERNEL_PREFILL_DOWN, st); launch_prefill_down(s, p, L.max_items, st); }
+    { ProfScope t(ctx, MOE_KERNEL_PREFILL_COMBINE, st); launch_prefill_combine(s, p, st); }
     if (s.S > 0) {
         // shared experts stay 16-bit (section 3.4.2): chunks of tokens through the bf16 kernels,
         // added to y; the intermediate keeps a bf16 remainder as in the draft call

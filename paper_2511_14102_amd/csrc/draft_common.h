@@ -179,7 +179,7 @@ inline FusedArgs fused_args(const Shape &s, const DraftFusedArgs &d)
     a.status = d.status; a.spin_limit = d.spin_limit;
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
-    a.items = d.items; a.n_items = d.n_items; a.sorted = d.sorted; a.w_all = d.w_all;
+    a.items = nullptr; a.n_items = nullptr; a.sorted = nullptr; a.w_all = nullptr;
     a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;
     return a;
 }

@@ -750,20 +750,6 @@ void launch_slice_t(const uint16_t *x, const FusedArgs &a, hipStream_t st, int n
 
 }  // namespace
 
-void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &d, int max_items, hipStream_t st)
-{
-    const FusedArgs a = fused_args(s, d);
-    const uint16_t *x = (const uint16_t *)d.x;
-    if (d.symmetric) launch_slice_t<kPrefillChunk, true, true>(x, a, st, max_items);
-    else launch_slice_t<kPrefillChunk, false, true>(x, a, st, max_items);
-}
-
-bool draft_prefill_fits(const Shape &s)
-{
-    // 160 KiB of LDS per workgroup, 20 KiB of them for the kernel's static arrays
-    return slice_dynamic_lds(kPrefillChunk, s.H, s.g, s.E, false) <= (size_t)(160 - 20) * 1024;
-}
-
 // one token: router inside the launch, one workgroup per (selected expert, slice)
 void launch_draft_one_token(const Shape &s, const DraftFusedArgs &d, hipStream_t st)
 {

@@ -100,16 +100,13 @@ void launch_route_plan(const Shape &s, const void *x, const void *wr, const floa
                        double *logits, uint32_t *token_arrivals, uint32_t *arrivals, hipStream_t st);
 // plan of the S shared experts alone over s.T tokens
 void launch_shared_plan(const Shape &s, Plan *plan, const void *shared, size_t shared_stride, hipStream_t st);
-struct PrefillItem;
-void launch_prefill_plan(const int32_t *ids, int n, int E, int32_t *sorted, PrefillItem *items,
-                         int32_t *n_items, hipStream_t st);
 void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
                   uint64_t *mask, int32_t *list, int32_t *n_list,
                   int32_t *missing, int32_t *n_missing, hipStream_t st);
 
-// Work item of an already routed draft call: up to kPrefillChunk assignments of one expert,
-// sorted[first .. first + cnt).
-constexpr int kPrefillChunk = 8;
+// Work item of the draft call over a long run of tokens: up to kPrefillChunk assignments of one
+// expert, sorted[first .. first + cnt).  Item i owns slots [64 i, 64 i + cnt).
+constexpr int kPrefillChunk = 64;
 struct PrefillItem { int32_t expert, first, cnt, pad; };
 
 // draft_int4.hip (a call of 2 to 8 tokens) and draft_slice.hip (one token; a routed run of tokens)
@@ -121,7 +118,6 @@ struct DraftFusedArgs {
     uint32_t *status; uint32_t spin_limit;
     float *y; int32_t *ids_out; float *conf_out;
     Plan *plan; const void *shared; size_t shared_stride;
-    const PrefillItem *items; const int32_t *n_items; const int32_t *sorted; const float *w_all;   // prerouted only
 };
 // n_cu: compute units of the device (the launch is persistent, at most one workgroup per unit)
 void launch_draft_fused(const Shape &s, const DraftFusedArgs &a, int n_cu, hipStream_t st);
@@ -130,16 +126,32 @@ bool draft_fits(const Shape &s, int tokens, bool symmetric);
 // whether the workgroups of the call's launch that reduce the router rows are all resident at once
 // (occupancy of the kernel the call will run x compute units)
 bool draft_producers_resident(const Shape &s, const DraftFusedArgs &a, int n_cu);
-// draft_slice.hip: one workgroup per (expert, slice) work item
-// grid sized for max_items work items; y must have been cleared
-void launch_draft_prerouted(const Shape &s, const DraftFusedArgs &a, int max_items, hipStream_t st);
-bool draft_prefill_fits(const Shape &s);
-// the call with ONE token (router inside the launch)
+// draft_slice.hip: the call with ONE token (router inside the launch), one workgroup per
+// (expert, slice) work item
 void launch_draft_one_token(const Shape &s, const DraftFusedArgs &a, hipStream_t st);
 bool draft_one_token_fits(const Shape &s);
 int draft_one_token_resident(const Shape &s, const DraftFusedArgs &a, int n_cu);   // workgroups resident at once
 void launch_zero(void *p, size_t bytes, hipStream_t st);
 void launch_stream_read(const void *src, size_t bytes, int workgroups, void *sink, hipStream_t st);
+
+// draft_prefill.hip: a routed run of tokens.  Byte sizes of the buffers a call with at most
+// max_items work items needs (h_plane: each of the two planes of h), then the launches in order.
+struct PrefillBuffers { size_t xt, x_sums, h_plane, h_sums, obuf; };
+PrefillBuffers prefill_buffers(const moe_layer_desc &d, int max_items);
+struct PrefillCall {
+    const void *x;                     // [T,H] bf16
+    const void *q, *sz; size_t stride_q, stride_sz; int symmetric;
+    const PrefillItem *items; const int32_t *n_items; const int32_t *sorted; const int32_t *slot_of;
+    const float *w_all;                // routing weight of every assignment [T k]
+    void *xt; float *x_sums; void *h_hi, *h_lo; float *h_sums; float *obuf;
+    float *y;                          // [T,H] fp32, written (not accumulated)
+};
+void launch_prefill_plan(const int32_t *ids, int n, int E, int32_t *sorted, int32_t *slot_of,
+                         PrefillItem *items, int32_t *n_items, hipStream_t st);
+void launch_prefill_stage(const Shape &s, const PrefillCall &p, int max_items, hipStream_t st);
+void launch_prefill_gateup(const Shape &s, const PrefillCall &p, int max_items, hipStream_t st);
+void launch_prefill_down(const Shape &s, const PrefillCall &p, int max_items, hipStream_t st);
+void launch_prefill_combine(const Shape &s, const PrefillCall &p, hipStream_t st);
 
 // expert_bf16.hip
 // hb_lo != nullptr: the intermediate is kept as a bf16 hi + lo pair (draft-pass precision)

@@ -189,47 +189,6 @@ void perm_kernel(const int32_t *__restrict__ ids, int n, int E, int32_t *count, 
     histogram_perm(s_ids, n, E, count, off, perm, s_count);
 }
 
-// Work list of an already routed draft call over many tokens: the n = T k assignments grouped
-// by expert (sorted[]; the order inside an expert is the order the atomics happened to take,
-// which no result depends on: a row's sums do not depend on the other rows of its item) and cut
-// into items of at most `chunk` assignments of one expert.  One workgroup.
-__global__ __launch_bounds__(1024)
-void prefill_plan_kernel(const int32_t *__restrict__ ids, int n, int E, int chunk,
-                         int32_t *__restrict__ sorted, PrefillItem *__restrict__ items, int32_t *__restrict__ n_items)
-{
-    __shared__ int32_t s_count[MOE_MAX_EXPERTS], s_off[MOE_MAX_EXPERTS], s_fill[MOE_MAX_EXPERTS],
-        s_item0[MOE_MAX_EXPERTS];
-    for (int e = threadIdx.x; e < E; e += blockDim.x) { s_count[e] = 0; s_fill[e] = 0; }
-    __syncthreads();
-    for (int a = threadIdx.x; a < n; a += blockDim.x) atomicAdd(&s_count[ids[a]], 1);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int off = 0, it = 0;
-        for (int e = 0; e < E; ++e) {
-            s_off[e] = off;
-            s_item0[e] = it;
-            off += s_count[e];
-            it += (s_count[e] + chunk - 1) / chunk;
-        }
-        *n_items = it;
-    }
-    __syncthreads();
-    for (int a = threadIdx.x; a < n; a += blockDim.x) {
-        const int e = ids[a];
-        sorted[s_off[e] + atomicAdd(&s_fill[e], 1)] = a;
-    }
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        const int c = s_count[e];
-        for (int j = 0; j * chunk < c; ++j) {
-            PrefillItem it;
-            it.expert = e; it.first = s_off[e] + j * chunk;
-            it.cnt = c - j * chunk < chunk ? c - j * chunk : chunk;
-            it.pad = 0;
-            items[s_item0[e] + j] = it;
-        }
-    }
-}
-
 // Plan that runs only the S shared experts over T tokens (rows n .. n + S T, n = T k routed rows
 // that stay dead): what the draft kernel leaves for the shared-expert kernels, for callers that
 // route elsewhere.
@@ -559,12 +518,6 @@ void launch_route_plan(const Shape &s, const void *x, const void *wr, const floa
 void launch_shared_plan(const Shape &s, Plan *plan, const void *shared, size_t shared_stride, hipStream_t st)
 {
     launch(shared_plan_kernel, dim3(1), dim3(256), 0, st, plan, s.T, s.k, s.S, s.E, (const char *)shared, shared_stride);
-}
-
-void launch_prefill_plan(const int32_t *ids, int n, int E, int32_t *sorted, PrefillItem *items,
-                         int32_t *n_items, hipStream_t st)
-{
-    launch(prefill_plan_kernel, dim3(1), dim3(1024), 0, st, ids, n, E, kPrefillChunk, sorted, items, n_items);
 }
 
 void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,

@@ -163,7 +163,7 @@ def test_draft_layer_symmetric_format(ctx, name):
 @pytest.mark.parametrize("name,tokens", [("tiny", (1, 9, 37, 200)), ("qwen3", (40,)), ("phi", (48,)),
                                          ("dsv2lite", (5, 45))])
 def test_draft_prefill(ctx, name, tokens):
-    # many tokens in one call: routed first, grouped by expert, 8 assignments of an expert per item
+    # many tokens in one call: routed first, grouped by expert, up to 64 assignments of an expert per item
     cfg = synth.config_by_name(name)
     say("building", cfg.name, "for prefill")
     L = build_layer(cfg)
@@ -185,7 +185,8 @@ def test_draft_prefill(ctx, name, tokens):
             r1 = D.draft(x.cuda())
             torch.cuda.synchronize()
             assert torch.equal(r1["ids"], r["ids"])
-            assert rel_err(to_np(r1["y"]), to_np(r["y"])) <= 1e-5
+            # two kernels with different fp32 summation orders, each within TOL_DRAFT of the oracle
+            assert rel_err(to_np(r1["y"]), to_np(r["y"])) <= 1e-4
     # a second call reuses the workspace (nothing is carried over) and a draft call still works after it
     r2 = D.prefill(x.cuda())
     torch.cuda.synchronize()
