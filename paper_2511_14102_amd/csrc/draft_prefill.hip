@@ -65,187 +65,247 @@ __device__ inline uint32_t load_entry(const char *szb, int H, int I, int g, int 
     }
 }
 
-template <bool DOWN, bool SYM, int KPG>
-__global__ __launch_bounds__(kTileThreads, (DOWN || KPG == 4) ? 3 : 2)
+template <bool DOWN, bool SYM, int KPG, int RB>
+__global__ __launch_bounds__(kTileThreads, 2)
 void prefill_tile_kernel(TileArgs a, int max_items)
 {
     constexpr int NP = DOWN ? 2 : 1;             // operand planes (h and its remainder)
     constexpr int SK = DOWN ? 2 : 4;             // k-steps per stage
     constexpr int NT = SK * NP * 4;              // operand tiles per stage (16 KiB)
-    constexpr int kSumsOff = NT * 1024;          // then SK x 64 fp32 sums
+    constexpr int GS = KPG < SK ? KPG : SK;      // k-steps per row of sums
+    constexpr int NR = SK / GS;                  // rows of sums per stage
+    constexpr int kSumsOff = NT * 1024;          // then NR x 64 fp32 sums
     constexpr int kStageBytes = kSumsOff + SK * 256;
     __shared__ __align__(16) unsigned char s_stage[2][kStageBytes];
 
-    const int item = blockIdx.x % max_items, tile = blockIdx.x / max_items;
+    // RB weight tiles per workgroup (gate/up: slices; down: row tiles of 64), tile0 the first
+    const int item = blockIdx.x % max_items, tile0 = (blockIdx.x / max_items) * RB;
     if (item >= *a.n_items) return;
     const PrefillItem it = a.items[item];
     const int tid = threadIdx.x, lane = tid & 63, r = lane & 15, c = lane >> 4;
-    const int d = __builtin_amdgcn_readfirstlane(tid >> 6);           // this wave's row block
+    const int d = __builtin_amdgcn_readfirstlane(tid >> 6);           // this wave's row block in every tile
     const int H = a.H, I = a.I, g = 32 * KPG;
     const int nk = DOWN ? I / 32 : H / 32, nfull = nk / SK;
+    const int ntiles = DOWN ? H / 64 : I / 32;
     const UnpackConsts uk = unpack_consts();
 
+    // a tile past the end repeats the last one (its results are dropped)
+    auto tile_of = [&](int rb) { return tile0 + rb < ntiles ? tile0 + rb : ntiles - 1; };
     const char *wq = a.q + (size_t)it.expert * a.stride_q + (DOWN ? (size_t)(I / 32) * (H / 32) * 1024 : 0) +
                      lane * 16 + 4 * d;
-    auto wstep = [&](int u) -> size_t {
-        return DOWN ? ((size_t)u * (H / 64) + tile) * 1024 : ((size_t)tile * (H / 32) + u) * 1024;
+    auto wstep = [&](int rb, int u) -> size_t {
+        return DOWN ? ((size_t)u * (H / 64) + tile_of(rb)) * 1024 : ((size_t)tile_of(rb) * (H / 32) + u) * 1024;
     };
     const char *szb = a.sz + (size_t)it.expert * a.stride_sz;
     const size_t step0 = (size_t)item * nk;
-    f32x4 tot[4];
+    f32x4 tot[RB][4];
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) tot[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) tot[rb][tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     // The whole K loop for an item with NTB token blocks (a compile-time count: no branch inside
     // a stage, so the LDS reads of a stage are issued ahead of its MFMAs).
-    auto run = [&](auto ntb_c) {
+    // kAct: this wave's token block exists (d < NTB), so it stages operand tiles and sums; the
+    // waves of absent blocks only take part in the weights.  Both are compile-time properties of
+    // the code a wave runs, and the loads of a stage are unconditional (past the end they repeat
+    // the last stage): a load inside a branch makes the compiler wait for ALL loads in flight
+    // where the branch joins, which would undo the two-stage pipeline.
+    auto run = [&](auto ntb_c, auto act_c) {
         constexpr int NTB = decltype(ntb_c)::value;
-        // what one thread moves per stage: its wave's token block of every operand tile, the code
-        // dword and the entry of its row block for every k-step, and 16 bytes of the sums
-        u32x4 st_act[SK * NP];
-        uint32_t st_w[SK], st_e[SK], cur_w[SK], cur_e[SK];
-        f32x4 st_sum = {0.f, 0.f, 0.f, 0.f};
-        const bool sum_thread = tid < 16 * SK && (tid & 15) / 4 < NTB;
-        auto load_stage = [&](int n) {
+        constexpr bool kAct = decltype(act_c)::value;
+        // What one thread moves per stage: its wave's token block of every operand tile, the code
+        // dword and the entry of its row block for every tile and k-step, and 16 bytes of one
+        // sums row (a row adds up the GS k-steps of a group that lie in the stage).  Two stages
+        // are in flight: set R[P] is loaded two stages ahead and written to LDS one stage ahead.
+        struct Stage { u32x4 act[SK * NP]; uint32_t w[RB][SK], e[RB][SK]; f32x4 sum[GS]; };
+        Stage R[2];
+        uint32_t cur_w[RB][SK], cur_e[RB][SK];
+        const int sum_row = (lane >> 2) & (NR - 1), sum_piece = lane & 3;   // this lane's 16 bytes of the sums
+        auto load_stage = [&](int n, Stage &S) {
 #pragma unroll
             for (int s = 0; s < SK; ++s) {
                 const int u = n * SK + s < nk ? n * SK + s : nk - 1;
-                if (d < NTB) {
+                if constexpr (kAct) {
 #pragma unroll
                     for (int p = 0; p < NP; ++p)
-                        st_act[s * NP + p] = *reinterpret_cast<const u32x4 *>(
+                        S.act[s * NP + p] = *reinterpret_cast<const u32x4 *>(
                             (p == 0 ? a.act0 : a.act1) + ((step0 + u) * 4 + d) * 1024 + lane * 16);
                 }
-                st_w[s] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(wq + wstep(u)));
-                st_e[s] = load_entry<DOWN, SYM>(szb, H, I, g, tile, u / KPG, r, d);
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb) {
+                    S.w[rb][s] = *reinterpret_cast<const uint32_t *>(wq + wstep(rb, u));
+                    S.e[rb][s] = load_entry<DOWN, SYM>(szb, H, I, g, tile_of(rb), u / KPG, r, d);
+                }
             }
-            if (sum_thread) {
-                const int u = n * SK + tid / 16 < nk ? n * SK + tid / 16 : nk - 1;
-                st_sum = *reinterpret_cast<const f32x4 *>(a.sums + (step0 + u) * 64 + 4 * (tid & 15));
+            if constexpr (kAct) {
+                // sums of this wave's token block: rows lie inside [0, nk) or outside as a whole; added
+                // up when they go to LDS (adding here would make the wave wait for the loads)
+                const int u0 = n * SK + sum_row * GS < nk ? n * SK + sum_row * GS : nk - GS;
+#pragma unroll
+                for (int j = 0; j < GS; ++j)
+                    S.sum[j] = *reinterpret_cast<const f32x4 *>(a.sums + (step0 + u0 + j) * 64 + 16 * d + 4 * sum_piece);
             }
         };
-        auto store_stage = [&](int b) {
-            if (d < NTB) {
+        auto store_stage = [&](int b, const Stage &S) {
+            if constexpr (kAct) {
 #pragma unroll
                 for (int j = 0; j < SK * NP; ++j)
-                    *reinterpret_cast<u32x4 *>(&s_stage[b][(j * 4 + d) * 1024 + lane * 16]) = st_act[j];
-            }
-            if (sum_thread)
-                *reinterpret_cast<f32x4 *>(&s_stage[b][kSumsOff + (tid / 16) * 256 + (tid & 15) * 16]) = st_sum;
+                    *reinterpret_cast<u32x4 *>(&s_stage[b][(j * 4 + d) * 1024 + lane * 16]) = S.act[j];
+                f32x4 v = S.sum[0];
 #pragma unroll
-            for (int s = 0; s < SK; ++s) { cur_w[s] = st_w[s]; cur_e[s] = st_e[s]; }
+                for (int j = 1; j < GS; ++j) v += S.sum[j];
+                if (lane < 4 * NR)
+                    *reinterpret_cast<f32x4 *>(&s_stage[b][kSumsOff + sum_row * 256 + (16 * d + 4 * sum_piece) * 4]) = v;
+            }
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int s = 0; s < SK; ++s) { cur_w[rb][s] = S.w[rb][s]; cur_e[rb][s] = S.e[rb][s]; }
         };
-        f32x4 acc[NTB], xs[NTB];
+        f32x4 acc[RB][NTB], xs[NTB];
 #pragma unroll
         for (int tb = 0; tb < NTB; ++tb) {
-            acc[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
             xs[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) acc[rb][tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
-        auto group_end = [&](uint32_t ev) {                       // scale, zero point, offset
-            const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(ev & 0xffff));
-            const float zp = SYM ? 136.f : (float)__builtin_bit_cast(_Float16, (uint16_t)(ev >> 16)) + 128.f;
-            const float nsz = -sc * zp;
+        auto group_end = [&](int s) {                             // scale, zero point, offset
 #pragma unroll
-            for (int tb = 0; tb < NTB; ++tb) {
+            for (int rb = 0; rb < RB; ++rb) {
+                const uint32_t ev = cur_e[rb][s];
+                const float sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(ev & 0xffff));
+                const float zp = SYM ? 136.f : (float)__builtin_bit_cast(_Float16, (uint16_t)(ev >> 16)) + 128.f;
+                const float nsz = -sc * zp;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    tot[tb][i] = fmaf(sc, acc[tb][i], tot[tb][i]);
-                    tot[tb][i] = fmaf(nsz, xs[tb][i], tot[tb][i]);
+                for (int tb = 0; tb < NTB; ++tb) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        tot[rb][tb][i] = fmaf(sc, acc[rb][tb][i], tot[rb][tb][i]);
+                        tot[rb][tb][i] = fmaf(nsz, xs[tb][i], tot[rb][tb][i]);
+                    }
+                    acc[rb][tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
                 }
-                acc[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                xs[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
+#pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) xs[tb] = (f32x4){0.f, 0.f, 0.f, 0.f};
         };
-        // k-steps [n SK, n SK + steps) from LDS buffer n & 1
-        auto compute_stage = [&](int n, int steps) {
+        // the k-steps of stage n from LDS buffer n & 1; full: all SK of them exist
+        auto compute_stage = [&](int n, auto full) {
+            constexpr bool kFull = decltype(full)::value;
             const unsigned char *buf = s_stage[n & 1];
 #pragma unroll
             for (int s = 0; s < SK; ++s) {
-                if (s < steps) {
-                    const bf16x8 wb = unpack8(cur_w[s], uk);
+                if (kFull || n * SK + s < nk) {
+                    bf16x8 wb[RB];
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb) wb[rb] = unpack8(cur_w[rb][s], uk);
 #pragma unroll
                     for (int tb = 0; tb < NTB; ++tb) {
 #pragma unroll
                         for (int p = 0; p < NP; ++p) {
                             const u32x4 xa = *reinterpret_cast<const u32x4 *>(&buf[((s * NP + p) * 4 + tb) * 1024 + lane * 16]);
-                            acc[tb] = mfma(xa, wb, acc[tb]);
+#pragma unroll
+                            for (int rb = 0; rb < RB; ++rb) acc[rb][tb] = mfma(xa, wb[rb], acc[rb][tb]);
                         }
-                        xs[tb] += *reinterpret_cast<const f32x4 *>(&buf[kSumsOff + s * 256 + (16 * tb + 4 * c) * 4]);
+                        if ((s + 1) % GS == 0)
+                            xs[tb] += *reinterpret_cast<const f32x4 *>(&buf[kSumsOff + (s / GS) * 256 + (16 * tb + 4 * c) * 4]);
                     }
                     if constexpr (KPG <= SK) {
-                        if ((s + 1) % KPG == 0) group_end(cur_e[s]);
+                        if ((s + 1) % KPG == 0) group_end(s);
                     } else {
-                        if (s == SK - 1 && (n & (KPG / SK - 1)) == KPG / SK - 1) group_end(cur_e[s]);
+                        if (s == SK - 1 && (n & (KPG / SK - 1)) == KPG / SK - 1) group_end(s);
                     }
                 }
             }
         };
+        const int ns = (nk + SK - 1) / SK;
+        auto iteration = [&](int n, auto parity) {
+            constexpr int P = decltype(parity)::value;
+            load_stage(n + 2 < ns ? n + 2 : ns - 1, R[P]);
+            if (n < nfull) compute_stage(n, std::true_type{});
+            else compute_stage(n, std::false_type{});
+            if (n + 1 < ns) store_stage((n + 1) & 1, R[P ^ 1]);
+            __syncthreads();
+        };
 
-        load_stage(0);
-        store_stage(0);
+        load_stage(0, R[0]);
+        load_stage(ns > 1 ? 1 : 0, R[1]);
+        store_stage(0, R[0]);
         __syncthreads();
-        for (int n = 0; n < nfull; ++n) {
-            const bool more = (n + 1) * SK < nk;
-            if (more) load_stage(n + 1);
-            compute_stage(n, SK);
-            if (more) store_stage((n + 1) & 1);
-            __syncthreads();
+        int n = 0;
+        for (; n + 1 < ns; n += 2) {
+            iteration(n, std::integral_constant<int, 0>{});
+            iteration(n + 1, std::integral_constant<int, 1>{});
         }
-        if (nfull * SK < nk) {                                    // ragged last stage (nk is even)
-            compute_stage(nfull, nk - nfull * SK);
-            __syncthreads();
-        }
+        if (n < ns) iteration(n, std::integral_constant<int, 0>{});
     };
     const int ntb = (it.cnt + 15) >> 4;
-    if (ntb == 4) run(std::integral_constant<int, 4>{});
-    else if (ntb == 3) run(std::integral_constant<int, 3>{});
-    else if (ntb == 2) run(std::integral_constant<int, 2>{});
-    else run(std::integral_constant<int, 1>{});
+    auto run_role = [&](auto ntb_c) {
+        if (d < decltype(ntb_c)::value) run(ntb_c, std::true_type{});
+        else run(ntb_c, std::false_type{});
+    };
+    if (ntb == 4) run(std::integral_constant<int, 4>{}, std::true_type{});
+    else if (ntb == 3) run_role(std::integral_constant<int, 3>{});
+    else if (ntb == 2) run_role(std::integral_constant<int, 2>{});
+    else run_role(std::integral_constant<int, 1>{});
 
-    // lane (r, c) of wave d now holds, per token block, rows d x 16 + r of tokens 4 c + i
+    // lane (r, c) of wave d now holds, per tile and token block, rows d x 16 + r of tokens 4 c + i
     if constexpr (DOWN) {
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
+        for (int rb = 0; rb < RB; ++rb) {
+            if (tile0 + rb >= ntiles) break;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int tok = 16 * tb + 4 * c + i;
-                if (tok < it.cnt) a.obuf[((size_t)item * kItemTokens + tok) * H + 64 * tile + 16 * d + r] = tot[tb][i];
+            for (int tb = 0; tb < 4; ++tb) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int tok = 16 * tb + 4 * c + i;
+                    if (tok < it.cnt)
+                        a.obuf[((size_t)item * kItemTokens + tok) * H + 64 * (tile0 + rb) + 16 * d + r] = tot[rb][tb][i];
+                }
             }
         }
     } else {
-        // pre-activations to LDS as [row block][token][r], then each wave turns one token block
-        // into its operand tiles: lane (token, chunk) holds h of inputs 8 chunk .. 8 chunk + 7
+        // one slice at a time: pre-activations to LDS as [row block][token][r], then each wave
+        // turns one token block into its operand tile: lane (token, chunk) holds h of inputs
+        // 8 chunk .. 8 chunk + 7
         float *s_out = reinterpret_cast<float *>(&s_stage[0][0]);       // 16 KiB
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
-            if (tb < ntb) {
+        for (int rb = 0; rb < RB; ++rb) {
+            if (tile0 + rb >= ntiles) break;                             // the same for the whole workgroup
+            if (rb > 0) __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 4; ++i) s_out[(d * 64 + 16 * tb + 4 * c + i) * 16 + r] = tot[tb][i];
-            }
-        }
-        __syncthreads();
-        if (d < ntb) {
-            const int tok = 16 * d + r;
-            uint32_t hi[4], lo[4];
-            float sum = 0.f;
+            for (int tb = 0; tb < 4; ++tb) {
+                if (tb < ntb) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int col = 8 * c + j, dd = col >> 4, rr = col & 15;
-                const float gate = s_out[(dd * 64 + tok) * 16 + rr], up = s_out[((2 + dd) * 64 + tok) * 16 + rr];
-                const float h = gate / (1.f + expf(-gate)) * up;
-                const uint32_t hb = f32_to_bf16_rne(h);
-                const float rest = h - __uint_as_float(hb << 16);
-                const uint32_t lb = f32_to_bf16_rne(rest);
-                sum += __uint_as_float(hb << 16) + __uint_as_float(lb << 16);
-                if (j & 1) { hi[j >> 1] |= hb << 16; lo[j >> 1] |= lb << 16; }
-                else { hi[j >> 1] = hb; lo[j >> 1] = lb; }
+                    for (int i = 0; i < 4; ++i) s_out[(d * 64 + 16 * tb + 4 * c + i) * 16 + r] = tot[rb][tb][i];
+                }
             }
-            const size_t t = (((size_t)item * (I / 32) + tile) * 4 + d) * 1024 + lane * 16;
-            *reinterpret_cast<u32x4 *>(a.h_hi + t) = (u32x4){hi[0], hi[1], hi[2], hi[3]};
-            *reinterpret_cast<u32x4 *>(a.h_lo + t) = (u32x4){lo[0], lo[1], lo[2], lo[3]};
-            sum += __shfl_xor(sum, 16);
-            sum += __shfl_xor(sum, 32);
-            if (c == 0) a.h_sums[((size_t)item * (I / 32) + tile) * 64 + tok] = sum;
+            __syncthreads();
+            if (d < ntb) {
+                const int tok = 16 * d + r;
+                uint32_t hi[4], lo[4];
+                float sum = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int col = 8 * c + j, dd = col >> 4, rr = col & 15;
+                    const float gate = s_out[(dd * 64 + tok) * 16 + rr], up = s_out[((2 + dd) * 64 + tok) * 16 + rr];
+                    const float h = gate / (1.f + expf(-gate)) * up;
+                    const uint32_t hb = f32_to_bf16_rne(h);
+                    const float rest = h - __uint_as_float(hb << 16);
+                    const uint32_t lb = f32_to_bf16_rne(rest);
+                    sum += __uint_as_float(hb << 16) + __uint_as_float(lb << 16);
+                    if (j & 1) { hi[j >> 1] |= hb << 16; lo[j >> 1] |= lb << 16; }
+                    else { hi[j >> 1] = hb; lo[j >> 1] = lb; }
+                }
+                const size_t slice = (size_t)item * (I / 32) + tile0 + rb;
+                const size_t t = (slice * 4 + d) * 1024 + lane * 16;
+                *reinterpret_cast<u32x4 *>(a.h_hi + t) = (u32x4){hi[0], hi[1], hi[2], hi[3]};
+                *reinterpret_cast<u32x4 *>(a.h_lo + t) = (u32x4){lo[0], lo[1], lo[2], lo[3]};
+                sum += __shfl_xor(sum, 16);
+                sum += __shfl_xor(sum, 32);
+                if (c == 0) a.h_sums[slice * 64 + tok] = sum;
+            }
         }
     }
 }
@@ -340,13 +400,16 @@ void prefill_combine_kernel(const float *__restrict__ obuf, const int32_t *__res
     *reinterpret_cast<f32x4 *>(y + (size_t)t * H + col) = acc;
 }
 
+constexpr int kRowBlocks = 2;                     // weight tiles per workgroup of the tile kernel
+
 template <bool DOWN, bool SYM>
 void launch_tile_g(const TileArgs &t, int tiles, int max_items, hipStream_t st)
 {
-    const dim3 grid((unsigned)((size_t)tiles * max_items)), block(kTileThreads);
-    if (t.g == 32) launch(prefill_tile_kernel<DOWN, SYM, 1>, grid, block, 0, st, t, max_items);
-    else if (t.g == 64) launch(prefill_tile_kernel<DOWN, SYM, 2>, grid, block, 0, st, t, max_items);
-    else launch(prefill_tile_kernel<DOWN, SYM, 4>, grid, block, 0, st, t, max_items);
+    const int cols = (tiles + kRowBlocks - 1) / kRowBlocks;
+    const dim3 grid((unsigned)((size_t)cols * max_items)), block(kTileThreads);
+    if (t.g == 32) launch(prefill_tile_kernel<DOWN, SYM, 1, kRowBlocks>, grid, block, 0, st, t, max_items);
+    else if (t.g == 64) launch(prefill_tile_kernel<DOWN, SYM, 2, kRowBlocks>, grid, block, 0, st, t, max_items);
+    else launch(prefill_tile_kernel<DOWN, SYM, 4, kRowBlocks>, grid, block, 0, st, t, max_items);
 }
 
 template <bool DOWN>
