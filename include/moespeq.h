@@ -32,8 +32,8 @@
  * (its copy and group sums), plus 12 E + 8 bytes of routing scratch when E > 32 (H <= 65536).  Two to
  * eight tokens, T rounded up to 2, 4 or 8: T (2 H + 16 + 4 H / g) + 12 T E bytes (rounded up to 16) plus
  * 16 KiB x (ceil(ceil(H / g / 8) / 4) + ceil(ceil(H / 64 / 8) / 4)) for the scale / zero entries of one
- * work item (in the symmetric format H / g and H / 64 count pairs).  The prefill call needs
- * 8 (2 H + 16 + 4 H / g) bytes.
+ * work item (in the symmetric format H / g and H / 64 count pairs).  The prefill call keeps a fixed
+ * 34 KiB whatever the shape.
  *
  * Kernel-native weight layouts (part of the ABI; pack.py builds them from row-major arrays)
  *
@@ -141,7 +141,7 @@ const char *moe_last_hip_error(const moe_ctx *ctx);
  * MOE_ERR_INVALID_ARG.  Needs no device. */
 int moe_validate_desc(const moe_layer_desc *desc);
 
-/* MOE_OK if a draft call with T tokens (1 .. MOE_MAX_DRAFT_TOKENS; the prefill call counts as 8)
+/* MOE_OK if a draft call with T tokens (1 .. MOE_MAX_DRAFT_TOKENS; the prefill call always fits)
  * fits the LDS limit stated above for this shape, else MOE_ERR_INVALID_ARG.  Needs no device. */
 int moe_draft_call_fits(const moe_layer_desc *desc, int T);
 
@@ -281,12 +281,17 @@ int moe_draft_layer_int4_noalloc(moe_ctx *ctx, const moe_layer_desc *desc,
  * int4 layer and choose its backend for the prefill stage as well as the decode stage (the
  * figure comparing backends there).  Same mathematics, arguments and outputs as moe_draft_layer_int4 for 1 <= T <=
  * MOE_MAX_PREFILL_TOKENS tokens.  All tokens are routed first, the assignments are grouped by
- * expert, and every expert's weights are streamed once per 8 of its assignments (a
- * token-by-token loop streams them once per assignment); shared experts run over chunks of up
- * to 16 tokens.
- * ids_out [T,k] and conf_out [T,k] (or NULL) as in moe_draft_layer_int4; y_f32 [T,H] is
- * cleared and then summed with fp32 atomics.  workspace: moe_prefill_workspace_bytes(desc, T)
- * bytes, 256-byte aligned, no state is kept in it between calls.
+ * expert and cut into work items of up to 64, and every expert's weights are streamed once per
+ * item (a token-by-token loop streams them once per assignment): a gate/up contraction per
+ * (item, 64 intermediate rows) leaves h in the workspace, a down contraction per (item, 128
+ * output rows) leaves each assignment's output there, and a last kernel adds up a token's k
+ * outputs in assignment order.  No kernel adds into memory that another workgroup writes, so
+ * y does not depend on the order in which workgroups run.  Shared experts run over chunks of
+ * up to 16 tokens and are added last.
+ * ids_out [T,k] and conf_out [T,k] (or NULL) as in moe_draft_layer_int4; y_f32 [T,H] is written.
+ * workspace: moe_prefill_workspace_bytes(desc, T) bytes (it grows with T k (3 H + 2 I) x 2 bytes
+ * for the operand tiles and outputs of the items), 256-byte aligned, no state is kept in it
+ * between calls.
  */
 int moe_prefill_workspace_bytes(const moe_layer_desc *desc, int T, size_t *bytes);
 int moe_draft_prefill_int4(moe_ctx *ctx, const moe_layer_desc *desc,

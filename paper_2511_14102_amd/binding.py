@@ -15,6 +15,7 @@ MOE_VERIFY_ACCUMULATE = 1
 MOE_VERIFY_ONLY_LISTED = 2
 MOE_VERIFY_STRICT = 4
 MOE_DRAFT_OK, MOE_DRAFT_TIMED_OUT = 0, 1
+MOE_MAX_TOKENS, MOE_MAX_DRAFT_TOKENS, MOE_MAX_PREFILL_TOKENS = 16, 8, 4096
 MOE_OK, MOE_ERR_INVALID_ARG, MOE_ERR_WORKSPACE, MOE_ERR_HIP, MOE_ERR_MISSING_EXPERT = 0, -1, -2, -3, -4
 
 EXPORTS = [

@@ -109,12 +109,6 @@ struct FusedArgs {
     Plan *plan;                 // filled for the shared-expert kernels when S > 0
     const char *shared;         // bf16 shared expert blobs
     size_t shared_stride;
-    // already routed call (a long run of tokens): work items, their number, the assignment indices
-    // sorted by expert, and the routing weight of every assignment
-    const PrefillItem *items;
-    const int32_t *n_items;
-    const int32_t *sorted;
-    const float *w_all;
     int T, H, E, I, k, g, S, renorm;
 };
 
@@ -179,7 +173,6 @@ inline FusedArgs fused_args(const Shape &s, const DraftFusedArgs &d)
     a.status = d.status; a.spin_limit = d.spin_limit;
     a.ids_out = d.ids_out; a.conf_out = d.conf_out; a.plan = d.plan;
     a.shared = (const char *)d.shared; a.shared_stride = d.shared_stride;
-    a.items = nullptr; a.n_items = nullptr; a.sorted = nullptr; a.w_all = nullptr;
     a.T = s.T; a.H = s.H; a.E = s.E; a.I = s.I; a.k = s.k; a.g = s.g; a.S = s.S; a.renorm = s.renorm;
     return a;
 }

@@ -596,14 +596,10 @@ void draft_stream_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                         __builtin_amdgcn_sched_barrier(0);
                         if (!kGuard || ku < u1) {
                             const u32x4 xn = *reinterpret_cast<const u32x4 *>(xrow + (ku + 1 < u1 ? ku + 1 : ku) * 32);
-#ifdef MOE_EXP_NOCOMPUTE
-                            acc[0][0] += __uint_as_float(qv.x ^ qv.y ^ qv.z ^ qv.w);
-#else
                             acc[0] = mfma(xa, b0, acc[0]);
                             acc[1] = mfma(xa, b1, acc[1]);
                             acc[2] = mfma(xa, b2, acc[2]);
                             acc[3] = mfma(xa, b3, acc[3]);
-#endif
                             xa = xn;
                             if (i % UPG == UPG - 1) {                 // end of a group: scale / zero / offset
                                 const int gi = ku / UPG;
@@ -649,9 +645,7 @@ void draft_stream_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
                     for (int i = 0; i < NI; ++i) s_red[wave][d][i][c * 16 + r] = tot[d][i];
             }
-#ifndef MOE_EXP_NOBARRIER
             __syncthreads();
-#endif
             if (it - it_begin < 2) STAMP(6 + 4 * (it - it_begin));
             // h for (token slot, row): row blocks 0, 1 are gate rows 0-15, 16-31; 2, 3 the matching up rows
             for (int idx = tid; idx < 2 * NI * NC * 16; idx += kThreads) {
@@ -680,9 +674,7 @@ void draft_stream_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
                 if (!last) item_rows(nxt.expert, par ^ 1);
                 if (lane < MT) s_hsum[par ^ 1][lane] = 0.f;
             }
-#ifndef MOE_EXP_NOBARRIER
             __syncthreads();
-#endif
             if (it - it_begin < 2) STAMP(7 + 4 * (it - it_begin));
 
             // ---- down: this wave's row tiles, all H outputs of the slice's 32 columns.
@@ -747,12 +739,8 @@ void draft_stream_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 #pragma unroll
                             for (int q = 0; q < 4 / kBpa; ++q) {
                                 f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
-#ifdef MOE_EXP_NOCOMPUTE
-                                o[0] = __uint_as_float(qv.x ^ qv.y ^ qv.z ^ qv.w);
-#else
 #pragma unroll
                                 for (int bl = 0; bl < kBpa; ++bl) o = mfma(hab[bl], b[q * kBpa + bl], o);
-#endif
                                 const int d = q * kBpa + my_bl;          // this lane's row block of the tile
                                 float sc, zp;
                                 if constexpr (kOwnEntry) {

@@ -17,12 +17,9 @@ namespace moespeq {
 namespace {
 
 // MT: token capacity of the launch (1, 2, 4 or 8); UPG: 32-code units per group (g / 32); SYM:
-// symmetric format (scale blobs, z = 8).  PRE: the tokens are already routed and sorted by expert
-// (a prompt, or any run of more than MOE_MAX_DRAFT_TOKENS tokens): workgroup b takes slice
-// b % (I / 32) of work item b / (I / 32) from a list, an item being up to MT assignments of one
-// expert; its rows are gathered from x, y has been cleared by the caller, and the router
-// exchange (phases 1, 2, 4, 5) does not take place.
-template <int MT, int UPG, bool SYM, bool PRE>
+// symmetric format (scale blobs, z = 8).  Only MT = 1 is instantiated: calls of two to eight
+// tokens run the streaming kernel, longer runs the grouped contraction.
+template <int MT, int UPG, bool SYM>
 __global__ __launch_bounds__(kThreads, MT <= 2 ? 4 : 2)   // MT <= 2: 4 waves per SIMD, two workgroups per CU
 void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 {
@@ -40,7 +37,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     __shared__ int32_t s_row_a[MT];             // assignment index of each row (token) of this item
     __shared__ int32_t s_cnt;
     __shared__ int32_t s_flag;
-    __shared__ double s_few[PRE ? 1 : MT][kLoneWaveTopk];   // few experts: a token's logits for the ranking
+    __shared__ double s_few[MT][kLoneWaveTopk];   // few experts: a token's logits for the ranking
     // partial gate/up sums [wave][row block][token in lane group][lane].  With 8 tokens the array
     // (16 KiB) takes the place of the x copy, which is no longer needed by then: the workgroup's LDS
     // then stays under half of a compute unit's, so that two workgroups share a unit.
@@ -66,22 +63,13 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     const size_t logit_off = ((size_t)MT * xstride * 2 + (size_t)MT * G * 4 + 7) & ~(size_t)7;
     double *s_logit = reinterpret_cast<double *>(s_dyn + logit_off);
     int32_t *s_rank = reinterpret_cast<int32_t *>(s_dyn + logit_off + (size_t)MT * E * 8);
-    int pre_expert = -1, pre_cnt = 0;
-    if constexpr (PRE) {
-        const int item = blockIdx.x / (I / 32);
-        if (item >= *a.n_items) return;                   // the grid is sized for the largest possible list
-        const PrefillItem it = a.items[item];
-        pre_expert = it.expert;
-        pre_cnt = it.cnt < MT ? it.cnt : MT;
-        if (tid < MT) s_row_a[tid] = a.sorted[it.first + (tid < pre_cnt ? tid : 0)];
-    }
     // ---- 1. router rows owned by this workgroup (fp64 accumulation of exact fp32 products)
-    if (!PRE && (int)blockIdx.x < E) {
+    if ((int)blockIdx.x < E) {
         const int nprod = E < (int)gridDim.x ? E : (int)gridDim.x;
         for (int i = blockIdx.x * kThreads + tid; i < T * H; i += nprod * kThreads)
             __hip_atomic_store(&a.y[i], 0.f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    for (int e = blockIdx.x; !PRE && e < E; e += gridDim.x) {
+    for (int e = blockIdx.x; e < E; e += gridDim.x) {
         const uint16_t *row = a.wr + (size_t)e * H;
         for (int t = 0; t < T; ++t) {
             const uint16_t *xt = xin + (size_t)t * H;
@@ -121,11 +109,10 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     __syncthreads();
 
     // ---- 1b. (while the router result travels) stage x in LDS and sum it per group
-    // (PRE: LDS row j is the token of the item's j-th assignment)
-    const int Ts = PRE ? pre_cnt : T;
+    const int Ts = T;
     for (int i = tid; i < Ts * (H / 8); i += kThreads) {
         const int t = i / (H / 8), c8 = i % (H / 8);
-        const int src = PRE ? s_row_a[t] / k : t;
+        const int src = t;
         *reinterpret_cast<u32x4 *>(s_x + t * xstride + c8 * 8) = *reinterpret_cast<const u32x4 *>(xin + (size_t)src * H + c8 * 8);
     }
     __syncthreads();
@@ -143,7 +130,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     // ---- 2. wave t polls the slots of token t (bounded), then selects its top-k
     double sm_logit = -INFINITY;                 // few experts: this lane's logit and rank, for the softmax later
     int sm_rank = MOE_MAX_EXPERTS;
-    for (int t = wave; !PRE && t < T; t += kWaves) {
+    for (int t = wave; t < T; t += kWaves) {
         double l[4];
         {
             uint32_t spins = 0;
@@ -212,7 +199,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             }
         }
     }
-    if (!PRE && E > kLoneWaveTopk) {
+    if (E > kLoneWaveTopk) {
         // Ranks in the order (larger first, lower index first among equals), counted by all eight
         // waves, each over its share of the experts; the order is strict, so rank < k selects.  (k
         // rounds of arg-max in the one wave of a token took 5.4 us for 128 experts and k = 8.)
@@ -266,7 +253,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
     __syncthreads();
-    const bool ok = PRE || s_flag != 0;
+    const bool ok = s_flag != 0;
     // This workgroup will not look at the slots again: it will draw a ticket.  The tickets are
     // two-level (kTicketGroups first-level counters, then one) so that the returning atomics do
     // not queue up on one address (measured: up to 5 us with one counter).  The compiler turns the
@@ -278,15 +265,15 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     // the kernel's end, when the loads behind the ticket wait for it in the return queue instead).
     uint32_t ticket = 0xffffffffu;
     auto draw_ticket = [&]() {
-        if (!PRE && tid == kThreads - 64)
+        if (tid == kThreads - 64)
             ticket = __hip_atomic_fetch_add(a.tickets + blockIdx.x % kTicketGroups, 1u, __ATOMIC_RELAXED,
                                             __HIP_MEMORY_SCOPE_AGENT);
     };
     // ---- 3. this workgroup's item: the u-th distinct expert (ascending id), slice s
     const int nslice = I / 32;
     const int u = blockIdx.x / nslice, slice = blockIdx.x % nslice;
-    int expert = pre_expert;
-    if (!PRE && ok) {
+    int expert = -1;
+    if (ok) {
         int seen = 0;
         for (int wd = 0; wd < MOE_MAX_EXPERTS / 64 && expert < 0; ++wd) {
             unsigned long long mk = s_mask[wd];
@@ -404,7 +391,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
     // the softmax of wave t's token (few experts), off the path to the first weight load: the
     // selection compared the fp64 logits; the softmax values only have to be good to fp32, so they
     // are computed in fp32 from the fp64 differences
-    if (!PRE && E <= kLoneWaveTopk && wave < T && ok) {
+    if (E <= kLoneWaveTopk && wave < T && ok) {
         const int t = wave;                      // T <= kWaves: one token per wave
         const double mx = wave::max(sm_logit);
         const float pe = lane < E ? expf((float)(sm_logit - mx)) : 0.f;
@@ -417,10 +404,10 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         }
     }
     // ---- 3b. the rows (tokens) of the item
-    if (tid == 0) s_cnt = pre_cnt;
+    if (tid == 0) s_cnt = 0;
     if (tid < MT) s_hsum[tid] = 0.f;
     __syncthreads();
-    if (!PRE && expert >= 0 && wave == 0) {     // rows of the item: assignments with this expert, ascending
+    if (expert >= 0 && wave == 0) {     // rows of the item: assignments with this expert, ascending
         int cnt = 0;
         for (int base = 0; base < n; base += 64) {
             const int aidx = base + lane;
@@ -440,7 +427,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
 
     if (expert >= 0 && cnt > 0) {
         // A-operand row of this lane: token slot r (slots >= cnt repeat slot 0; their D rows are ignored)
-        auto lds_row = [&](int slot) { return PRE ? slot : s_row_a[slot] / k; };   // where the slot's x was staged
+        auto lds_row = [&](int slot) { return s_row_a[slot] / k; };   // where the slot's x was staged
         const uint16_t *xrow = s_x + lds_row(r < cnt ? r : 0) * xstride + c * 8;
         // tokens whose results this lane holds in its D registers: slot 4c + i
         int tok[NI];
@@ -618,7 +605,7 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
             live[i] = t < cnt;
             hsum[i] = s_hsum[slot];
             tokd[i] = arow / k;
-            rwd[i] = PRE ? a.w_all[arow] : s_w[arow];
+            rwd[i] = s_w[arow];
         }
         // one pass over the window: kReload: the slot is refilled with the tile kGuWin further on
         // (clamped, unconditional); the last pass refills nothing
@@ -680,7 +667,6 @@ void draft_fused_kernel(const uint16_t *__restrict__ xin, const FusedArgs a)
         down_pass(j0, std::false_type{});
     }
 
-    if constexpr (PRE) return;
     // ---- 4. last ticket: every workgroup has its logits, put the workspace back to idle
     if (tid == kThreads - 64) {
         const uint32_t grp = blockIdx.x % kTicketGroups;
@@ -738,14 +724,14 @@ size_t slice_dynamic_lds(int MT, int H, int g, int E, bool routed)
     return lds;
 }
 
-template <int MT, bool SYM, bool PRE>
+template <int MT, bool SYM>
 void launch_slice_t(const uint16_t *x, const FusedArgs &a, hipStream_t st, int n_groups_of_slices)
 {
     const dim3 grid(n_groups_of_slices * (a.I / 32)), block(kThreads);
-    const size_t lds = slice_dynamic_lds(MT, a.H, a.g, a.E, !PRE);
-    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM, PRE>, grid, block, lds, st, x, a);
-    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM, PRE>, grid, block, lds, st, x, a);
-    else launch_with_lds(draft_fused_kernel<MT, 4, SYM, PRE>, grid, block, lds, st, x, a);
+    const size_t lds = slice_dynamic_lds(MT, a.H, a.g, a.E, true);
+    if (a.g == 32) launch_with_lds(draft_fused_kernel<MT, 1, SYM>, grid, block, lds, st, x, a);
+    else if (a.g == 64) launch_with_lds(draft_fused_kernel<MT, 2, SYM>, grid, block, lds, st, x, a);
+    else launch_with_lds(draft_fused_kernel<MT, 4, SYM>, grid, block, lds, st, x, a);
 }
 
 }  // namespace
@@ -756,8 +742,8 @@ void launch_draft_one_token(const Shape &s, const DraftFusedArgs &d, hipStream_t
     const FusedArgs a = fused_args(s, d);
     const uint16_t *x = (const uint16_t *)d.x;
     const int experts = a.E < a.k ? a.E : a.k;
-    if (d.symmetric) launch_slice_t<1, true, false>(x, a, st, experts);
-    else launch_slice_t<1, false, false>(x, a, st, experts);
+    if (d.symmetric) launch_slice_t<1, true>(x, a, st, experts);
+    else launch_slice_t<1, false>(x, a, st, experts);
 }
 
 int draft_one_token_resident(const Shape &s, const DraftFusedArgs &d, int n_cu)
@@ -766,13 +752,13 @@ int draft_one_token_resident(const Shape &s, const DraftFusedArgs &d, int n_cu)
     int per = 0;
     auto ask = [&](auto kernel) { per = resident_per_cu(kernel, kThreads, lds); };
     if (d.symmetric) {
-        if (s.g == 32) ask(draft_fused_kernel<1, 1, true, false>);
-        else if (s.g == 64) ask(draft_fused_kernel<1, 2, true, false>);
-        else ask(draft_fused_kernel<1, 4, true, false>);
+        if (s.g == 32) ask(draft_fused_kernel<1, 1, true>);
+        else if (s.g == 64) ask(draft_fused_kernel<1, 2, true>);
+        else ask(draft_fused_kernel<1, 4, true>);
     } else {
-        if (s.g == 32) ask(draft_fused_kernel<1, 1, false, false>);
-        else if (s.g == 64) ask(draft_fused_kernel<1, 2, false, false>);
-        else ask(draft_fused_kernel<1, 4, false, false>);
+        if (s.g == 32) ask(draft_fused_kernel<1, 1, false>);
+        else if (s.g == 64) ask(draft_fused_kernel<1, 2, false>);
+        else ask(draft_fused_kernel<1, 4, false>);
     }
     return per * n_cu;
 }

@@ -391,16 +391,25 @@ def test_argument_errors_enqueue_nothing(ctx, tiny):
     assert B.validate_desc(big) == 0
     buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
     ws = torch.zeros(B.workspace_bytes(big, 8), dtype=torch.uint8, device="cuda")
-    for T, what in ((8, "draft"), (19, "prefill")):
+    with pytest.raises(B.MoeError) as ei:
+        ctx.draft_layer_int4(big, buf, buf, None, buf, buf, B.int4_expert_q_bytes(big),
+                             B.int4_expert_sz_bytes(big), None, 8, buf, buf, None, ws)
+    assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    # the call over a long run of tokens (no LDS limit; real buffers of the tiny layer): too many
+    # tokens, then a workspace that is too small
+    xp = synth.make_tokens(tiny.cfg, 19).cuda()
+    yp = torch.empty((19, 256), dtype=torch.float32, device="cuda")
+    idp = torch.empty((19, tiny.cfg.top_k), dtype=torch.int32, device="cuda")
+    pws = torch.zeros(B.prefill_workspace_bytes(D.desc, 19), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.MoeError) as ei:
+        B.prefill_workspace_bytes(D.desc, B.MOE_MAX_PREFILL_TOKENS + 1)
+    assert ei.value.status == B.MOE_ERR_INVALID_ARG
+    for T, w, status in ((B.MOE_MAX_PREFILL_TOKENS + 1, pws, B.MOE_ERR_INVALID_ARG), (0, pws, B.MOE_ERR_INVALID_ARG),
+                         (19, pws[:4096], B.MOE_ERR_WORKSPACE)):
         with pytest.raises(B.MoeError) as ei:
-            if what == "draft":
-                ctx.draft_layer_int4(big, buf, buf, None, buf, buf, B.int4_expert_q_bytes(big),
-                                     B.int4_expert_sz_bytes(big), None, T, buf, buf, None, ws)
-            else:
-                pws = torch.zeros(B.prefill_workspace_bytes(big, T), dtype=torch.uint8, device="cuda")
-                ctx.draft_prefill_int4(big, buf, buf, None, buf, buf, B.int4_expert_q_bytes(big),
-                                       B.int4_expert_sz_bytes(big), None, T, buf, buf, None, pws)
-        assert ei.value.status == B.MOE_ERR_INVALID_ARG, what
+            ctx.draft_prefill_int4(D.desc, xp, D.router, D.bias, D.q_blob, D.sz_blob, D.q_bytes, D.sz_bytes,
+                                   D.shared, T, yp, idp, None, w)
+        assert ei.value.status == status, (T, status)
     torch.cuda.synchronize()
 
 
