@@ -1,15 +1,21 @@
-// Draft pass over a long run of already routed tokens (the prompt): the SwiGLU FFN of the selected
-// experts on group-wise int4 weights, work items of up to 8 assignments of one expert (gfx950).
+// Draft-pass kernel for a call with ONE token: router, top-k and the SwiGLU FFN of the selected
+// experts on group-wise int4 weights in one launch, one workgroup per work item (gfx950).
+// (Calls of two to eight tokens run the persistent kernel of draft_int4.hip, longer runs of
+// tokens the grouped contraction of draft_prefill.hip.)
 //
-// Paper section 3.4.3 (one expert-fused kernel instead of per-expert small GEMMs, the backend
-// comparison for the prefill stage), section 4.1.3 (4-bit weights in groups along the input
-// dimension).  The arithmetic is described in draft_common.h.
+// Paper section 3.4.3 (one expert-fused kernel instead of per-expert small GEMMs), section 4.1.3
+// (4-bit weights in groups along the input dimension), section 3.3.1 (expert id and confidence
+// for the lookahead buffer).  The arithmetic is described in draft_common.h, the
+// cross-workgroup protocol of the router exchange in draft_int4.hip (the same here).
 //
 // Work decomposition ("slice fusion").  A work item is (expert, slice of 32 intermediate
 // rows): its workgroup computes the 32 gate and 32 up pre-activations (K = H split over the 8
 // waves by groups), h = silu(gate) * up, and immediately multiplies h into the 32 matching
 // columns of the down projection for all H outputs, adding the partial outputs into y with
-// fp32 atomics.
+// fp32 atomics.  With one token a call has k I / 32 items (400 on the phi shape), about one
+// and a half per compute unit: one workgroup per item, two resident per unit, was measured
+// faster here than a persistent launch (26 against 28 us), whose per-item latency chain a
+// stream of only one or two items cannot hide.
 #include "draft_common.h"
 
 namespace moespeq {
