@@ -747,6 +747,52 @@ def offload_leg(args, cfg, ctx, dev):
     emit(cfg, args, K, T, n_layers, tb / n_layers, None, "eager, copies on a side stream", mean_u, nbytes, roofline, cpu, extra)
 
 
+def draft_table_leg(args, cfg, ctx, dev):
+    """--draft-table: the draft kernel's duration (kernel-stamped events) for calls of 1, 2, 4 and 8 tokens,
+    rotating over distinct layers, with the bytes each call has to move (the distinct experts its tokens
+    select, once each).  A side measurement: one JSON line, no headline metric."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2511_14102_amd.harness import DeviceLayer
+
+    sym = args.int4 == "symmetric"
+    H, E, I, k, g = cfg.hidden, cfg.n_experts, cfg.inter, cfg.top_k, cfg.group_size
+    P = 3 * H * I
+    expert_bytes = P // 2 + (P // g) * (2 if sym else 4)
+    n_layers = args.layers or (12 if expert_bytes * E < 2e9 else 6)
+    layers = [DeviceLayer(ctx, cfg, synth.make_layer(cfg, li, device=dev, symmetric=sym), max_tokens=8, verify=False,
+                          symmetric=sym) for li in range(n_layers)]
+    xs = [synth.make_tokens(cfg, 8, layer=li).to(dev) for li in range(n_layers)]
+    ids = torch.empty((8, k), dtype=torch.int32, device=dev)
+    rows = {}
+    for T in (1, 2, 4, 8):
+        for i in range(n_layers):
+            layers[i].draft(xs[i][:T])
+        torch.cuda.synchronize()
+        distinct = []
+        ctx.profile_enable(True)
+        for i in range(8 * n_layers):
+            r = layers[i % n_layers].draft(xs[i % n_layers][(i // n_layers) % (9 - T):][:T], ids=ids[:T])
+            if i < n_layers:
+                distinct.append(len(set(r["ids"].cpu().numpy().reshape(-1).tolist())))
+        torch.cuda.synchronize()
+        prof = read_profile(ctx)
+        ctx.profile_enable(False)
+        us = prof["draft_fused_kernel"]["us_avg"]
+        n_calls = prof["draft_fused_kernel"]["launches"]
+        call_us = sum(v["us_avg"] for v in prof.values() if v["launches"] == n_calls)   # + shared-expert kernels, if any
+        nbytes = float(np.mean(distinct)) * expert_bytes + E * H * 2 + T * H * 2 + T * H * 4
+        rows[str(T)] = {"us": round(us, 2), "all_kernels_of_the_call_us": round(call_us, 2),
+                        "mean_distinct_experts": round(float(np.mean(distinct)), 2),
+                        "bytes": int(nbytes), "GBs": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                        "launches": n_calls}
+    print(json.dumps({"metric": "draft kernel duration by tokens per call, 1 GPU", "unit": "us", "data": "synthetic",
+                      "config": {"workload": "%s-shaped MoE layer, %d distinct layers rotating, int4 %s" %
+                                 (cfg.name, n_layers, "symmetric" if sym else "asymmetric")},
+                      "tokens_per_call": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -760,6 +806,8 @@ def main():
                     help="draft weight format: scale + zero per group (default) or scales only with z = 8")
     ap.add_argument("--prefill", type=int, default=0,
                     help="side measurement: one moe_draft_prefill_int4 call over this many tokens per step")
+    ap.add_argument("--draft-table", action="store_true",
+                    help="side measurement: the draft kernel's duration for calls of 1, 2, 4 and 8 tokens")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--slots", type=int, default=0,
@@ -780,7 +828,9 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.config_by_name(args.config)
     ctx = B.Context(0)
-    if args.prefill:
+    if args.draft_table:
+        draft_table_leg(args, cfg, ctx, "cuda:0")
+    elif args.prefill:
         prefill_leg(args, cfg, ctx, "cuda:0")
     elif cfg.n_resident and cfg.n_resident < cfg.n_experts:
         offload_leg(args, cfg, ctx, "cuda:0")

@@ -375,8 +375,7 @@ static int enqueue_draft(moe_ctx *ctx, const moe_layer_desc *desc, const void *x
         launch_draft_fused(s, a, ctx->n_cu, st);
         if (s.S > 0) {
             launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, ws + L.hb_lo, st);
-            launch_bf16_down(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, (float *)(ws + L.obuf), st);
-            launch_combine(s, plan, nullptr, 0, (const float *)(ws + L.obuf), 1, 0, y, st);
+            launch_bf16_down_add(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, y, st);
         }
         return hip_status(ctx, hipGetLastError());
     }
@@ -384,10 +383,10 @@ static int enqueue_draft(moe_ctx *ctx, const moe_layer_desc *desc, const void *x
     if (s.S > 0) {   // shared experts stay 16-bit in the draft model (section 3.4.2)
         { ProfScope p(ctx, MOE_KERNEL_BF16_GATEUP, st);
           launch_bf16_gateup(s, plan, 0, s.S, x, ws + L.hb, ws + L.hb_lo, st); }
+        // the down kernel adds the shared experts' outputs to y itself (fp32 atomics on top of
+        // the routed experts' sum): no combine launch
         { ProfScope p(ctx, MOE_KERNEL_BF16_DOWN, st);
-          launch_bf16_down(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, (float *)(ws + L.obuf), st); }
-        { ProfScope p(ctx, MOE_KERNEL_COMBINE, st);
-          launch_combine(s, plan, nullptr, 0, (const float *)(ws + L.obuf), 1, 0, y, st); }
+          launch_bf16_down_add(s, plan, 0, s.S, ws + L.hb, ws + L.hb_lo, y, st); }
     }
     return hip_status(ctx, hipGetLastError());
 }

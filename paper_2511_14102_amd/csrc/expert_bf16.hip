@@ -113,8 +113,10 @@ void bf16_gateup_kernel(const Plan *__restrict__ plan, int first_active,
 
 // obuf[row, r] = row_w[row] * (Wd h[row])[r] for 16 values of r.
 // grid.x = H / 16, grid.y = experts; block = 4 waves splitting K = I.
-// kHiLo: the operand is hb + hb_lo (two MFMAs per tile).
-template <bool kHiLo>
+// kHiLo: the operand is hb + hb_lo (two MFMAs per tile).  kAddY: instead of writing obuf, add the
+// row's outputs to y[token] with fp32 atomics (the draft call's shared experts: y already holds
+// the routed experts' sum, itself made of such atomics, so no combine launch is needed).
+template <bool kHiLo, bool kAddY>
 __global__ __launch_bounds__(kWaves * 64)
 void bf16_down_kernel(const Plan *__restrict__ plan, int first_active,
                       const uint16_t *__restrict__ hb, const uint16_t *__restrict__ hb_lo,
@@ -179,7 +181,14 @@ void bf16_down_kernel(const Plan *__restrict__ plan, int first_active,
         for (int w = 0; w < kWaves; ++w) v += s_red[w][i][lane];
         op[i] = v * rw;
     }
-    *reinterpret_cast<float4 *>(obuf + (size_t)(off + n) * H + blockIdx.x * 16 + c * 4) = o;
+    if constexpr (kAddY) {
+        float *yrow = obuf + (size_t)plan->row_tok[off + n] * H + blockIdx.x * 16 + c * 4;   // obuf is y here
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __hip_atomic_fetch_add(yrow + i, op[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        *reinterpret_cast<float4 *>(obuf + (size_t)(off + n) * H + blockIdx.x * 16 + c * 4) = o;
+    }
 }
 
 // Final sum per token in a fixed order: routed rows by rank j (each summed over the K-splits),
@@ -257,11 +266,20 @@ void launch_bf16_down(const Shape &s, const Plan *plan, int first_active, int n_
     if (n_active_max <= 0) return;
     const dim3 grid(s.H / 16, n_active_max), block(kWaves * 64);
     if (hb_lo)
-        launch(bf16_down_kernel<true>, grid, block, 0, st, plan, first_active,
+        launch(bf16_down_kernel<true, false>, grid, block, 0, st, plan, first_active,
                            (const uint16_t *)hb, (const uint16_t *)hb_lo, obuf, s.H, s.I);
     else
-        launch(bf16_down_kernel<false>, grid, block, 0, st, plan, first_active,
+        launch(bf16_down_kernel<false, false>, grid, block, 0, st, plan, first_active,
                            (const uint16_t *)hb, (const uint16_t *)nullptr, obuf, s.H, s.I);
+}
+
+void launch_bf16_down_add(const Shape &s, const Plan *plan, int first_active, int n_active_max,
+                          const void *hb, const void *hb_lo, float *y, hipStream_t st)
+{
+    if (n_active_max <= 0) return;
+    const dim3 grid(s.H / 16, n_active_max), block(kWaves * 64);
+    launch(bf16_down_kernel<true, true>, grid, block, 0, st, plan, first_active,
+                       (const uint16_t *)hb, (const uint16_t *)hb_lo, y, s.H, s.I);
 }
 
 void launch_combine(const Shape &s, const Plan *plan, const float *routed, int nsplit,

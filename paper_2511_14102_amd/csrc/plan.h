@@ -159,6 +159,10 @@ void launch_bf16_gateup(const Shape &s, const Plan *plan, int first_active, int 
                         const void *x, void *hb, void *hb_lo, hipStream_t st);
 void launch_bf16_down(const Shape &s, const Plan *plan, int first_active, int n_active_max,
                       const void *hb, const void *hb_lo, float *obuf, hipStream_t st);
+// the same product, each row's outputs added to y[row_tok[row]] (fp32, [T,H]) with atomics; the
+// intermediate is the bf16 hi + lo pair
+void launch_bf16_down_add(const Shape &s, const Plan *plan, int first_active, int n_active_max,
+                          const void *hb, const void *hb_lo, float *y, hipStream_t st);
 // y[t] = (accumulate ? y[t] : 0) + sum over the token's live routed rows of
 // sum_{split < nsplit} routed[split][row] + sum over its live shared rows of obuf[row];
 // routed is [nsplit][T*k][H] fp32, obuf is [rows][H] fp32 indexed by row number.
