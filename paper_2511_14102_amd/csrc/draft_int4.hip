@@ -828,8 +828,10 @@ void zero_kernel(uint32_t *p, size_t n)
 
 // Plain streaming read of `tiles` 1 KiB tiles with the access shape of the weight stream above:
 // every wave owns a contiguous run of tiles, a lane takes 16 bytes of a tile, kWin non-temporal
-// loads in flight per lane.  The words are folded so that the loads cannot be dropped; the fold
-// is stored only when it equals a value that memory holding real data will not produce.
+// loads in flight per lane, every load unconditional (past the end of the run it repeats the
+// last tile: a load under a branch would make the compiler drain the window at every step).
+// The words are folded so that the loads cannot be dropped; the fold is stored only when it
+// equals a value that memory holding real data will not produce.
 template <int kWin>
 __global__ __launch_bounds__(512, 2)
 void stream_read_kernel(const u32x4 *__restrict__ src, size_t tiles, uint32_t *sink)
@@ -840,20 +842,20 @@ void stream_read_kernel(const u32x4 *__restrict__ src, size_t tiles, uint32_t *s
     const size_t per = (tiles + nwaves - 1) / nwaves;
     const size_t first = wave * per;
     const size_t mine = first >= tiles ? 0 : (tiles - first < per ? tiles - first : per);
+    if (mine == 0) return;
     const u32x4 *q = src + first * 64 + lane;
     u32x4 win[kWin];
     uint32_t fold = 0;
 #pragma unroll
-    for (int i = 0; i < kWin; ++i)
-        if ((size_t)i < mine) win[i] = __builtin_nontemporal_load(q + (size_t)i * 64);
+    for (int i = 0; i < kWin; ++i) win[i] = __builtin_nontemporal_load(q + ((size_t)i < mine ? (size_t)i : mine - 1) * 64);
     for (size_t b = 0; b < mine; b += kWin) {
 #pragma unroll
         for (int i = 0; i < kWin; ++i) {
             const size_t t = b + i;
-            if (t < mine) {
-                fold ^= win[i].x ^ win[i].y ^ win[i].z ^ win[i].w;
-                if (t + kWin < mine) win[i] = __builtin_nontemporal_load(q + (t + kWin) * 64);
-            }
+            const u32x4 v = win[i];
+            const size_t nx = t + kWin < mine ? t + kWin : mine - 1;
+            win[i] = __builtin_nontemporal_load(q + nx * 64);
+            if (t < mine) fold ^= v.x ^ v.y ^ v.z ^ v.w;
         }
     }
     if (fold == 0x9E3779B9u) sink[0] = fold;
