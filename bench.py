@@ -793,6 +793,31 @@ def draft_table_leg(args, cfg, ctx, dev):
                       "tokens_per_call": rows}), flush=True)
 
 
+def read_probe_leg(args, cfg, ctx, dev):
+    """--read-probe: moe_stream_read_probe (a kernel that only reads) over the bytes of one one-token draft call,
+    cold data (the int4 blobs of distinct layers in rotation), for several grids: the draft kernel's own launch
+    shape (k I / 32 workgroups) and grids that fill the compute units evenly.  A side measurement."""
+    import torch
+    import synth
+    from paper_2511_14102_amd.harness import DeviceLayer
+
+    n_layers = args.layers or 12
+    layers = [DeviceLayer(ctx, cfg, synth.make_layer(cfg, li, device=dev), max_tokens=8, verify=False) for li in range(n_layers)]
+    blobs = [D.q_blob for D in layers]
+    nbytes = algorithmic_bytes(cfg, 1, 1.0)["draft_fused_kernel"]
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    own = cfg.top_k * cfg.inter // 32
+    rows = {}
+    for rep in range(3):                                     # three rounds: the scatter between them is part of the result
+        for grid in sorted({n_cu, own, 2 * n_cu, 2 * own, 4 * n_cu}):
+            r = stream_ceiling(ctx, torch, blobs, nbytes, grid, reps=96)
+            rows.setdefault(str(grid), []).append(r["us"])
+    print(json.dumps({"metric": "read-only kernel over the bytes of one draft call, 1 GPU", "unit": "us", "data": "synthetic",
+                      "config": {"workload": "%s-shaped MoE layer, %d distinct layers rotating" % (cfg.name, n_layers)},
+                      "bytes": nbytes // 1024 * 1024, "compute_units": n_cu, "draft_kernel_workgroups": own,
+                      "us_by_workgroups": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -808,6 +833,8 @@ def main():
                     help="side measurement: one moe_draft_prefill_int4 call over this many tokens per step")
     ap.add_argument("--draft-table", action="store_true",
                     help="side measurement: the draft kernel's duration for calls of 1, 2, 4 and 8 tokens")
+    ap.add_argument("--read-probe", action="store_true",
+                    help="side measurement: a kernel that only reads one draft call's bytes, for several grids")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--slots", type=int, default=0,
@@ -828,7 +855,9 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.config_by_name(args.config)
     ctx = B.Context(0)
-    if args.draft_table:
+    if args.read_probe:
+        read_probe_leg(args, cfg, ctx, "cuda:0")
+    elif args.draft_table:
         draft_table_leg(args, cfg, ctx, "cuda:0")
     elif args.prefill:
         prefill_leg(args, cfg, ctx, "cuda:0")
