@@ -21,8 +21,8 @@
 // I / 32 slices each) and this wins clearly over one workgroup per item (phi shape, 4 tokens:
 // 56 against 76 us, 8 tokens: 90 against 144 us; qwen3 shape, 8 tokens: 60 against 103 us).
 // With one token there are about one and a half items per compute unit on the phi shape, a
-// workgroup's stream is one or two items long, and the per-item latency chain (router exchange,
-// first loads, barrier with its skew, reduction, down tiles) is not hidden: 28 us against 26 us.
+// workgroup's stream is one or two items long, and there is nothing for it to overlap: 26.3 us
+// against 25.5 us for one workgroup per item, the same to 3 % on the other shapes.
 //
 // Cross-workgroup protocol (one bounded wait, no cache flushes):
 //   1. router row e is reduced by workgroup e (mod grid), which first clears its share of y
@@ -912,8 +912,9 @@ void launch_stream(int T, const uint16_t *x, const FusedArgs &a, int n_cu, hipSt
 void launch_draft_fused(const Shape &s, const DraftFusedArgs &d, int n_cu, hipStream_t st)
 {
     // One token: items are few (k I / 32, about one and a half per compute unit on the phi shape) and
-    // one workgroup per item is faster (26.1 us against 28.0 us for the persistent launch); from two
-    // tokens on the persistent launch wins (4 tokens: 56 against 76 us, 8 tokens: 90 against 144 us).
+    // one workgroup per item is as fast or a little faster (phi 25.5 us against 26.3 us for the
+    // persistent launch, mixtral 49.7 / 50.6, qwen3 18.9 / 19.5); from two tokens on the persistent
+    // launch wins (4 tokens: 56 against 76 us, 8 tokens: 90 against 144 us).
     if (s.T == 1) { launch_draft_one_token(s, d, st); return; }
     const FusedArgs a = fused_args(s, d);
     const uint16_t *x = (const uint16_t *)d.x;

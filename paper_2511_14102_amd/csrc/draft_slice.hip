@@ -14,8 +14,8 @@
 // columns of the down projection for all H outputs, adding the partial outputs into y with
 // fp32 atomics.  With one token a call has k I / 32 items (400 on the phi shape), about one
 // and a half per compute unit: one workgroup per item, two resident per unit, was measured
-// faster here than a persistent launch (26 against 28 us), whose per-item latency chain a
-// stream of only one or two items cannot hide.
+// as fast or a little faster here than a persistent launch (25.5 against 26.3 us), whose
+// continuous stream has nothing to overlap when it is only one or two items long.
 #include "draft_common.h"
 
 namespace moespeq {
