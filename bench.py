@@ -293,6 +293,24 @@ def resident_leg(args, cfg, ctx, dev):
         }
         extra["per_call"]["verify_tokens_per_s"] = round(T * 1e6 / extra["per_call"]["verify_us"], 1)
 
+    # ---- one isolated call, host clock from launch to completion (the per-call figures above are
+    # kernel times of back-to-back launches)
+    def latency(fn, reps=20):
+        out = []
+        for i in range(reps + 3):
+            li = i % n_layers
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            fn(li)
+            torch.cuda.synchronize()
+            if i >= 3:
+                out.append((time.perf_counter() - t) * 1e6)
+        return round(float(np.median(out)), 1)
+    extra["single_call_latency_us"] = {
+        "draft": latency(lambda li: layers[li].draft(xs[li][0:1], y=bufs[li]["yd"][0:1], ids=bufs[li]["win"][0:1], conf=bufs[li]["conf"][0:1])),
+        "verify": latency(lambda li: layers[li].verify(xs[li], y=bufs[li]["yv"], ids=bufs[li]["idv"])),
+        "note": "host wall clock of one call with a synchronise before and after, median of 20, layers rotating"}
+
     # ---- layer 0's step as the timed launches left it, against the oracle (same buffers, same path)
     if not args.no_cpu_baseline:
         from oracle.layer_check import oracle_arrays, oracle_draft, oracle_verify, rel_err
@@ -670,6 +688,7 @@ def offload_leg(args, cfg, ctx, dev):
         "layers": n_layers, "resident_per_layer": n_res, "slots_per_layer": n_slots, "cycles": cycles,
         "draft_launch": "one HIP graph per drafted token" if draft_graphs else "eager calls",
         "t_both_ms": round(tb, 3), "t_compute_ms": round(tc, 3), "t_copy_ms": round(tp, 3),
+        "overlap": round((tp + tc - tb) / min(tp, tc), 3),       # (t_copy + t_compute - t_both) / min(t_copy, t_compute)
         "compute_hidden_under_copies": round((tp + tc - tb) / min(tp, tc), 3),
         "timeline_last_cycle_ms": {n: (v if isinstance(v, dict) or v is None else round(v, 3)) for n, v in tl.items()},
         "draft_phase_hidden_under_copies": None if draft_hidden is None else round(draft_hidden, 3),
