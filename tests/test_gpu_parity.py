@@ -160,7 +160,7 @@ def test_draft_layer_symmetric_format(ctx, name):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name,tokens", [("tiny", (1, 9, 37, 200, 1500)), ("qwen3", (40,)), ("phi", (48,)),
+@pytest.mark.parametrize("name,tokens", [("tiny", (1, 9, 37, 200, 1500, 4096)), ("qwen3", (40,)), ("phi", (48,)),
                                          ("dsv2lite", (5, 45))])
 def test_draft_prefill(ctx, name, tokens):
     # many tokens in one call: routed first, grouped by expert, up to 64 assignments of an expert per item
