@@ -6,21 +6,22 @@
 //   prefill_plan_kernel    assignments sorted by expert, items, slot of every assignment
 //   prefill_stage_kernel   the items' tokens gathered into MFMA operand tiles (zero padded), and
 //                          the sum of each tile row (32 inputs), which the zero points need
-//   prefill_tile_kernel<gate/up>  one workgroup per (item, slice of 32 intermediate rows): 64
-//                          pre-activations (32 gate, 32 up) x 64 tokens over all of H,
-//                          h = silu(gate) * up written as operand tiles of a bf16 value and its
-//                          bf16 remainder, plus the tile row sums of h
-//   prefill_tile_kernel<down>     one workgroup per (item, 64 output rows): those rows x 64
-//                          tokens over all of I, written to a per-slot fp32 buffer
+//   prefill_tile_kernel<gate/up>  one workgroup per (item, two slices of 32 intermediate rows):
+//                          per slice 64 pre-activations (32 gate, 32 up) x 64 tokens over all of
+//                          H, h = silu(gate) * up written as operand tiles of a bf16 value and
+//                          its bf16 remainder, plus the tile row sums of h
+//   prefill_tile_kernel<down>     one workgroup per (item, two tiles of 64 output rows): those
+//                          rows x 64 tokens over all of I, written to a per-slot fp32 buffer
 //   prefill_combine_kernel y[t] = sum over the token's k assignments of weight x slot output
 //
 // No kernel adds into memory another workgroup writes: every output element has one owner, so
 // the result does not depend on the order in which workgroups run.
 //
-// The tile kernel.  Its four waves each own one block of 16 weight rows of the 64-row tile (the
-// dword of that block in every lane's 16 bytes of a code tile) and all four token blocks; the
-// token operand tiles of a stage of k-steps are staged through LDS once and read by all four
-// waves (double buffered, one barrier per stage).  Arithmetic as in the other draft kernels:
+// The tile kernel.  Its four waves each own one block of 16 weight rows in each of the
+// workgroup's 64-row weight tiles (the dword of that block in every lane's 16 bytes of a code
+// tile) and all four token blocks; the token operand tiles of a stage of k-steps are staged
+// through LDS once and read by all four waves (LDS double buffered, one barrier per stage; two
+// stages of global loads in flight).  Arithmetic as in the other draft kernels:
 // codes become the exact bf16 integers 128 + q, a group's products are summed by the matrix cores
 // (16x16x32 bf16, fp32 accumulate), and scale, zero point and the 128 offset are applied once per
 // group with the sum of the group's activations:  s * (acc - (z + 128) * sum).
