@@ -109,7 +109,7 @@ void launch_union(const int32_t *ids, int n_ids, int E, const int32_t *slot,
 constexpr int kPrefillChunk = 64;
 struct PrefillItem { int32_t expert, first, cnt, pad; };
 
-// draft_int4.hip (a call of 2 to 8 tokens) and draft_slice.hip (one token; a routed run of tokens)
+// draft_int4.hip (a call of 2 to 8 tokens) and draft_slice.hip (a call of one token)
 struct DraftFusedArgs {
     const void *x, *wr; const float *bias;
     const void *q, *sz; size_t stride_q, stride_sz;
